@@ -1,0 +1,160 @@
+/*
+ * gaf.h -- C ABI of libgaf: Gradient Agreement Filtering (GAF) aggregation of
+ * micro-gradients on one AMD MI355X (gfx950).
+ *
+ * The operation (paper: Sec. 3.1, Algorithm 1, Eq. 4, Eq. 5).  Given a
+ * sequence of N micro-gradients g_1..g_N, each a flat vector of P parameters,
+ * and a threshold tau:
+ *
+ *     g <- g_1, c <- 1
+ *     for i = 2..N:   D_i = 1 - (g . g_i) / (|g| |g_i|)          (Eq. 4)
+ *                     if D_i <= tau:  g <- g + g_i,  c <- c + 1   (Algorithm 1)
+ *     g_GAF = g / c                                               (Eq. 5)
+ *
+ * D_i is taken against the running aggregate of the gradients accepted so
+ * far. c == 1 at the end means that no two micro-gradients agreed; the paper
+ * then skips the optimizer step -- that decision is the caller's, the library
+ * reports c and still returns g_GAF = g_1.
+ *
+ * Conventions shared by every call
+ *   - Pointers marked DEVICE are addresses in the memory of the GPU the
+ *     context was created on; pointers marked HOST are ordinary host memory.
+ *     The library never takes ownership of a caller's buffer and never frees
+ *     one. It allocates device memory only inside gaf_create.
+ *   - Every call enqueues its kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and returns without waiting. Results
+ *     are valid once the caller has synchronised that stream. Input buffers
+ *     must stay valid and unmodified until then. No result is ever copied to
+ *     the host and the accept/reject decisions are taken on the device.
+ *   - The context's device must be the current HIP device of the calling
+ *     thread. One context serves one stream at a time: calls on the same
+ *     context from different streams or threads that may overlap on the GPU
+ *     race on the context's workspace.
+ *   - Vectors are contiguous. P may be any positive value (no multiple-of-4
+ *     requirement). DEVICE vector pointers (gradients, accumulator, out) must
+ *     be 16-byte aligned, otherwise GAF_EALIGN.
+ *   - The running aggregate is kept as the running MEAN of the accepted
+ *     gradients in binary32 (Eq. 4 does not change when one argument is
+ *     rescaled, so distances against the mean equal distances against the
+ *     paper's running sum; the mean makes the division of Eq. 5 implicit).
+ *     Inner products and norms are accumulated in binary64.
+ *   - Ties: D_i == tau accepts. A zero-norm operand gives D_i = 1 by
+ *     definition. A NaN distance (NaN or Inf in g_i) is stored as NaN and
+ *     rejects g_i; the aggregate is left bit-for-bit unchanged.
+ *     D_i is not clamped to [0, 2]. tau is compared in binary64.
+ *   - Determinism: for a given (P, dtype) the launch shape and every summation
+ *     order are fixed; no floating-point atomics are used. Repeating a call on
+ *     the same inputs gives bit-identical outputs.
+ *   - Errors are returned as gaf_status; nothing is thrown across the ABI.
+ *     On any status other than GAF_OK nothing was enqueued, except GAF_EHIP,
+ *     which reports a failed launch part-way (outputs are then undefined).
+ */
+#ifndef GAF_H
+#define GAF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GAF_OK = 0,
+    GAF_EINVAL = 1,       /* NULL where a pointer is required, N < 1, P == 0, sizes beyond the context's */
+    GAF_EALIGN = 2,       /* a DEVICE vector pointer is not 16-byte aligned */
+    GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace */
+    GAF_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
+    GAF_EUNSUPPORTED = 5, /* unknown dtype, or device is not the context's */
+    GAF_EDEVICE = 6       /* the context's device is not the calling thread's current device */
+} gaf_status;
+
+/* Element type of the micro-gradients. The aggregate and `out` are always binary32. */
+typedef enum {
+    GAF_F32 = 0,  /* IEEE binary32 */
+    GAF_BF16 = 1  /* bfloat16: the upper 16 bits of a binary32 */
+} gaf_dtype;
+
+typedef struct gaf_ctx gaf_ctx; /* opaque; owns only its own device workspace */
+
+/*
+ * Create a context on HIP device `device` able to serve calls with P <= max_P
+ * and N <= max_N. Allocates the workspace (per-block partial sums, the device
+ * decision state, and the partial Gram blocks gaf_pairwise needs).
+ * *ctx (HOST) receives the handle. The current device is left as it was.
+ */
+gaf_status gaf_create(gaf_ctx **ctx, int device, size_t max_P, int max_N);
+
+/* Free the workspace. The caller must have synchronised every stream that used the context. */
+gaf_status gaf_destroy(gaf_ctx *ctx);
+
+/* Static, never-freed description of a status code. */
+const char *gaf_strerror(gaf_status status);
+
+/*
+ * Batch aggregation of one macrobatch: Algorithm 1 from seeding to g / c
+ * (Sec. 3.1; Eq. 4 for the distance; Eq. 5 for the result).
+ *
+ *   grads        HOST array of N DEVICE pointers, each to P elements of `dt`.
+ *                grads[0] is the seed g_1 (the paper draws the seed at random:
+ *                the caller expresses that draw, and the visiting order, by
+ *                how it orders this array). Read-only.
+ *   tau          cosine-distance threshold; tau >= 2 admits everything and
+ *                gives the plain mean (Eq. 2), tau < 0 keeps only the seed.
+ *   out          DEVICE, P binary32: g_GAF. Also used as the running aggregate
+ *                while the call runs; must not alias any input.
+ *   accept_mask  DEVICE, N bytes: 1 if g_i was accepted, else 0; [0] = 1.
+ *   cos_dist     DEVICE, N binary32: D_i as computed when g_i was visited;
+ *                [0] = 0 (the seed is not compared with anything).
+ *   count        DEVICE, one int32: c, the number of accepted gradients (>= 1).
+ *
+ * HBM traffic per visited gradient: the aggregate is read once and g_i once
+ * for the distance; an accepted g_i is read a second time, in the same pass
+ * that reduces the next gradient, when the aggregate is rewritten.
+ */
+gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                         float tau, float *out, uint8_t *accept_mask, float *cos_dist,
+                         int32_t *count, void *stream);
+
+/*
+ * Streaming form: one visit of Algorithm 1's inner loop for a gradient that
+ * has just arrived. The state (accum, count) is DEVICE-resident, caller-owned,
+ * and carried from call to call.
+ *
+ *   accum         DEVICE, P binary32, in/out: running mean of the accepted
+ *                 gradients, i.e. g_GAF of everything seen so far.
+ *   count         DEVICE, one int32, in/out: c. *count == 0 means "nothing seen
+ *                 yet": g_i becomes the seed (accum <- g_i, c <- 1, reported
+ *                 distance 0, accepted) and the previous contents of accum are
+ *                 ignored.
+ *   g_i           DEVICE, P elements of `dt`, read-only.
+ *   cos_dist_out  DEVICE, one binary32, may be NULL: D_i.
+ *   accepted_out  DEVICE, one byte, may be NULL: 1 if accepted.
+ *
+ * Two kernels: the distance reduction with the decision taken by the last
+ * block to finish, then the conditional update, which exits at once when g_i
+ * was rejected.
+ */
+gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                    gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
+                    void *stream);
+
+/*
+ * Diagnostic: Eq. 4 between every pair of the N micro-gradients, the quantity
+ * the paper logs over training (Sec. 1, Fig. 1c/d).
+ *
+ *   grads  HOST array of N DEVICE pointers (as in gaf_aggregate).
+ *   D      DEVICE, N*N binary32, row-major: D[i*N+j] = D_c(g_i, g_j);
+ *          symmetric, diagonal exactly 0.
+ *   gram   DEVICE, N*N binary64, row-major, may be NULL: the inner products
+ *          g_i . g_j the distances were formed from.
+ *
+ * Every gradient is read once when N <= 64; for larger N, in 64-row panels.
+ */
+gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                        float *D, double *gram, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GAF_H */

@@ -1,0 +1,313 @@
+// libgaf: host side of the C ABI declared in include/gaf.h. Validates
+// arguments, sizes the launches (a fixed function of P, so results are
+// reproducible) and enqueues kernels on the caller's stream. It never
+// synchronises and never reads a device result.
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "../../include/gaf.h"
+#include "gaf_gram.hpp"
+#include "gaf_pass.hpp"
+
+using namespace gaf;
+
+struct gaf_ctx {
+    int device;
+    size_t max_P;
+    int max_N;
+    State *st;           // device
+    double *partials;    // device, [3][kMaxBlocks]
+    double *gram_ws;     // device, [kGramBlocks][3][kGramTile]
+    double *gram_full;   // device, [max_N][max_N]
+};
+
+namespace {
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Workgroups for a streaming pass over P elements: every workgroup gets the
+// same number of tiles (to within one), at most kMaxBlocks workgroups.
+inline int pass_blocks(size_t P)
+{
+    const size_t ntiles = (P + kTile - 1) / kTile;
+    const size_t iters = (ntiles + kMaxBlocks - 1) / kMaxBlocks;
+    return static_cast<int>((ntiles + iters - 1) / iters);
+}
+
+gaf_status check_ctx(const gaf_ctx *ctx)
+{
+    if (!ctx) return GAF_EINVAL;
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) return GAF_EHIP;
+    if (cur != ctx->device) return GAF_EDEVICE;
+    return GAF_OK;
+}
+
+inline gaf_status launched()
+{
+    return hipGetLastError() == hipSuccess ? GAF_OK : GAF_EHIP;
+}
+
+template <typename T>
+gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
+                          float *out, uint8_t *mask, float *cos_dist, int32_t *count,
+                          hipStream_t s)
+{
+    const dim3 grid(pass_blocks(P)), block(kBlock);
+    PassArgs a{};
+    a.P = P;
+    a.st = ctx->st;
+    a.partials = ctx->partials;
+    a.tau = tau;
+    a.dst = out;
+
+    if (N == 1) {
+        init_single_kernel<<<1, 1, 0, s>>>(ctx->st, cos_dist, mask);
+        if (launched() != GAF_OK) return GAF_EHIP;
+        a.pend = grads[0];
+        a.count_out = count;
+        update_kernel<T><<<grid, block, 0, s>>>(a);
+        return launched();
+    }
+
+    // pass 1: adopt the seed, reduce against grads[1]
+    a.pend = grads[0];
+    a.next = grads[1];
+    a.cos_out = cos_dist + 1;
+    a.mask_out = mask + 1;
+    a.count_out = count;
+    a.seed_outputs = 1;
+    seed_reduce_kernel<T><<<grid, block, 0, s>>>(a);
+    if (launched() != GAF_OK) return GAF_EHIP;
+
+    // passes 2..N-1: apply the decision on grads[i-1] while reducing against grads[i]
+    a.acc = out;
+    a.seed_outputs = 0;
+    a.count_in = &ctx->st->count;
+    for (int i = 2; i < N; ++i) {
+        a.pend = grads[i - 1];
+        a.next = grads[i];
+        a.cos_out = cos_dist + i;
+        a.mask_out = mask + i;
+        reduce_kernel<T><<<grid, block, 0, s>>>(a);
+        if (launched() != GAF_OK) return GAF_EHIP;
+    }
+
+    // tail: apply the decision on the last gradient (no traffic if it was rejected)
+    a.pend = grads[N - 1];
+    a.next = nullptr;
+    a.cos_out = nullptr;
+    a.mask_out = nullptr;
+    a.count_out = nullptr;
+    update_kernel<T><<<grid, block, 0, s>>>(a);
+    return launched();
+}
+
+template <typename T>
+gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                     float tau, float *cos_out, uint8_t *acc_out, hipStream_t s)
+{
+    const dim3 grid(pass_blocks(P)), block(kBlock);
+    PassArgs a{};
+    a.P = P;
+    a.st = ctx->st;
+    a.partials = ctx->partials;
+    a.tau = tau;
+    a.acc = accum;
+    a.dst = accum;
+    a.next = g_i;
+    a.count_in = count;
+    a.cos_out = cos_out;
+    a.mask_out = acc_out;
+    reduce_kernel<T><<<grid, block, 0, s>>>(a);
+    if (launched() != GAF_OK) return GAF_EHIP;
+    a.pend = g_i;
+    a.next = nullptr;
+    a.count_in = nullptr;
+    a.cos_out = nullptr;
+    a.mask_out = nullptr;
+    a.count_out = count;
+    update_kernel<T><<<grid, block, 0, s>>>(a);
+    return launched();
+}
+
+template <typename T>
+gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float *D,
+                         double *gram_out, hipStream_t s)
+{
+    const int ngroups = (N + 31) / 32;
+    auto launch = [&](int ga, int gb, int aa, int ab, int bb) -> gaf_status {
+        GramArgs g{};
+        for (int k = 0; k < 32; ++k) {
+            const int ia = ga * 32 + k, ib = gb * 32 + k;
+            g.rows[k] = ia < N ? grads[ia] : nullptr;
+            g.rows[32 + k] = (gb >= 0 && ib < N) ? grads[ib] : nullptr;
+        }
+        g.P = P;
+        g.ws = ctx->gram_ws;
+        g.do_aa = aa;
+        g.do_ab = ab;
+        g.do_bb = bb;
+        g.use_b = gb >= 0;
+        gram_kernel<T><<<kGramBlocks, kBlock, 0, s>>>(g);
+        if (launched() != GAF_OK) return GAF_EHIP;
+        GramFinalArgs f{};
+        f.ws = ctx->gram_ws;
+        f.nblocks = kGramBlocks;
+        f.gram = ctx->gram_full;
+        f.N = N;
+        f.row_a = ga * 32;
+        f.row_b = gb >= 0 ? gb * 32 : 0;
+        f.do_aa = aa;
+        f.do_ab = ab;
+        f.do_bb = bb;
+        gram_finalize_kernel<<<(3 * kGramTile + kBlock - 1) / kBlock, kBlock, 0, s>>>(f);
+        return launched();
+    };
+    // panels of two groups: diagonal tiles and the tile between the panel's groups
+    for (int ga = 0; ga < ngroups; ga += 2) {
+        const bool pair = ga + 1 < ngroups;
+        const gaf_status rc = launch(ga, pair ? ga + 1 : -1, 1, pair ? 1 : 0, pair ? 1 : 0);
+        if (rc != GAF_OK) return rc;
+    }
+    // tiles between groups of different panels
+    for (int ga = 0; ga < ngroups; ++ga)
+        for (int gb = ga + 1; gb < ngroups; ++gb) {
+            if (ga / 2 == gb / 2) continue;
+            const gaf_status rc = launch(ga, gb, 0, 1, 0);
+            if (rc != GAF_OK) return rc;
+        }
+    const int n2 = N * N;
+    gram_to_distance_kernel<<<(n2 + kBlock - 1) / kBlock, kBlock, 0, s>>>(ctx->gram_full, N, D,
+                                                                         gram_out);
+    return launched();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gaf_strerror(gaf_status status)
+{
+    switch (status) {
+    case GAF_OK: return "ok";
+    case GAF_EINVAL: return "invalid argument";
+    case GAF_EALIGN: return "device vector pointer is not 16-byte aligned";
+    case GAF_ENOMEM: return "out of device memory";
+    case GAF_EHIP: return "HIP runtime call or kernel launch failed";
+    case GAF_EUNSUPPORTED: return "unsupported element type";
+    case GAF_EDEVICE: return "context's device is not the current device";
+    }
+    return "unknown status";
+}
+
+gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
+{
+    if (!out_ctx || max_P == 0 || max_N < 1) return GAF_EINVAL;
+    *out_ctx = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess) return GAF_EHIP;
+    if (device < 0 || device >= ndev) return GAF_EINVAL;
+    int prev = 0;
+    if (hipGetDevice(&prev) != hipSuccess) return GAF_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return GAF_EHIP;
+
+    gaf_ctx *ctx = new (std::nothrow) gaf_ctx();
+    if (!ctx) {
+        (void)hipSetDevice(prev);
+        return GAF_ENOMEM;
+    }
+    ctx->device = device;
+    ctx->max_P = max_P;
+    ctx->max_N = max_N;
+    const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * 3 * kGramTile;
+    const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
+    bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->partials),
+                        sizeof(double) * 3 * kMaxBlocks) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->gram_ws), gram_ws_bytes) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->gram_full), gram_full_bytes) == hipSuccess;
+    ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
+    ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    (void)hipSetDevice(prev);
+    if (!ok) {
+        (void)hipGetLastError();
+        gaf_destroy(ctx);
+        return GAF_ENOMEM;
+    }
+    *out_ctx = ctx;
+    return GAF_OK;
+}
+
+gaf_status gaf_destroy(gaf_ctx *ctx)
+{
+    if (!ctx) return GAF_EINVAL;
+    int prev = 0;
+    const bool have_prev = hipGetDevice(&prev) == hipSuccess;
+    (void)hipSetDevice(ctx->device);
+    if (ctx->st) (void)hipFree(ctx->st);
+    if (ctx->partials) (void)hipFree(ctx->partials);
+    if (ctx->gram_ws) (void)hipFree(ctx->gram_ws);
+    if (ctx->gram_full) (void)hipFree(ctx->gram_full);
+    if (have_prev) (void)hipSetDevice(prev);
+    delete ctx;
+    return GAF_OK;
+}
+
+gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                         float tau, float *out, uint8_t *accept_mask, float *cos_dist,
+                         int32_t *count, void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!grads || N < 1 || P == 0 || !out || !accept_mask || !cos_dist || !count) return GAF_EINVAL;
+    if (N > ctx->max_N || P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (misaligned(out)) return GAF_EALIGN;
+    for (int i = 0; i < N; ++i) {
+        if (!grads[i] || grads[i] == static_cast<const void *>(out)) return GAF_EINVAL;
+        if (misaligned(grads[i])) return GAF_EALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return dt == GAF_F32
+               ? aggregate_impl<float>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+               : aggregate_impl<bf16_t>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+}
+
+gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                    gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
+                    void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!accum || !count || !g_i || P == 0 || g_i == static_cast<const void *>(accum))
+        return GAF_EINVAL;
+    if (P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (misaligned(accum) || misaligned(g_i)) return GAF_EALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return dt == GAF_F32
+               ? step_impl<float>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
+               : step_impl<bf16_t>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+}
+
+gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                        float *D, double *gram, void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!grads || N < 1 || P == 0 || !D) return GAF_EINVAL;
+    if (N > ctx->max_N || P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    for (int i = 0; i < N; ++i) {
+        if (!grads[i]) return GAF_EINVAL;
+        if (misaligned(grads[i])) return GAF_EALIGN;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return dt == GAF_F32 ? pairwise_impl<float>(ctx, grads, N, P, D, gram, s)
+                         : pairwise_impl<bf16_t>(ctx, grads, N, P, D, gram, s);
+}
+
+}  // extern "C"

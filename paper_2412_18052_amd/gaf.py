@@ -1,0 +1,174 @@
+"""Thin ctypes binding of libgaf.so (the C ABI in include/gaf.h).
+
+Argument marshalling only: torch tensors supply device pointers and the
+current stream; every step of the computation runs inside the HIP library.
+There is no CPU fallback: a missing library or a failing call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgaf.so")
+
+GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEVICE = range(7)
+GAF_F32, GAF_BF16 = 0, 1
+
+SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise")
+
+
+class GafError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (what, strerror(status), status))
+
+
+_lib = None
+
+
+def load(path=None):
+    """Load libgaf.so (building it with hipcc first if it has never been built)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    lib.gaf_create.restype = c.c_int
+    lib.gaf_create.argtypes = [c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int]
+    lib.gaf_destroy.restype = c.c_int
+    lib.gaf_destroy.argtypes = [c.c_void_p]
+    lib.gaf_strerror.restype = c.c_char_p
+    lib.gaf_strerror.argtypes = [c.c_int]
+    lib.gaf_aggregate.restype = c.c_int
+    lib.gaf_aggregate.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
+                                  c.c_float, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_void_p]
+    lib.gaf_step.restype = c.c_int
+    lib.gaf_step.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_int,
+                             c.c_float, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_pairwise.restype = c.c_int
+    lib.gaf_pairwise.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
+                                 c.c_void_p, c.c_void_p, c.c_void_p]
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load().gaf_strerror(int(status)).decode()
+
+
+def _check(status, what):
+    if status != GAF_OK:
+        raise GafError(status, what)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return GAF_F32
+    if t.dtype == torch.bfloat16:
+        return GAF_BF16
+    raise TypeError("gradients must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _grad_table(grads):
+    if len(grads) < 1:
+        raise ValueError("need at least one gradient")
+    P, code = grads[0].numel(), _dtype_code(grads[0])
+    for g in grads:
+        if not g.is_cuda or not g.is_contiguous() or g.dim() != 1 or g.numel() != P \
+                or _dtype_code(g) != code:
+            raise ValueError("gradients must be contiguous 1-D device tensors of one length and dtype")
+    table = (ctypes.c_void_p * len(grads))(*[g.data_ptr() for g in grads])
+    return table, P, code
+
+
+class Context:
+    """Owns a gaf_ctx handle (gaf_create / gaf_destroy)."""
+
+    def __init__(self, max_P, max_N, device=None):
+        device = torch.cuda.current_device() if device is None else int(device)
+        self.device = device
+        self._h = ctypes.c_void_p(0)
+        _check(load().gaf_create(ctypes.byref(self._h), device, int(max_P), int(max_N)), "gaf_create")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if self._h:
+            load().gaf_destroy(self._h)
+            self._h = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def gaf_create(max_P, max_N, device=None):
+    return Context(max_P, max_N, device)
+
+
+def gaf_destroy(ctx):
+    ctx.close()
+
+
+def gaf_strerror(status):
+    return strerror(status)
+
+
+def gaf_aggregate(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,
+                  stream=None):
+    """Enqueue the batch aggregation. Returns (out, accept_mask, cos_dist, count) device tensors;
+    valid after the stream is synchronised."""
+    table, P, code = _grad_table(grads)
+    dev = grads[0].device
+    N = len(grads)
+    out = torch.empty(P, dtype=torch.float32, device=dev) if out is None else out
+    accept_mask = torch.empty(N, dtype=torch.uint8, device=dev) if accept_mask is None else accept_mask
+    cos_dist = torch.empty(N, dtype=torch.float32, device=dev) if cos_dist is None else cos_dist
+    count = torch.empty(1, dtype=torch.int32, device=dev) if count is None else count
+    _check(load().gaf_aggregate(ctx.handle, table, N, P, code, float(tau), _ptr(out),
+                                _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
+                                _stream_handle(stream)), "gaf_aggregate")
+    return out, accept_mask, cos_dist, count
+
+
+def gaf_step(ctx, accum, count, g_i, tau, cos_dist_out=None, accepted_out=None, stream=None):
+    """Enqueue one streaming visit; (accum, count) are updated in place on the device."""
+    if not g_i.is_cuda or not g_i.is_contiguous() or g_i.dim() != 1:
+        raise ValueError("g_i must be a contiguous 1-D device tensor")
+    if accum.dtype != torch.float32 or accum.numel() != g_i.numel() or not accum.is_contiguous():
+        raise ValueError("accum must be contiguous float32 of the gradient's length")
+    if count.dtype != torch.int32 or count.numel() != 1:
+        raise ValueError("count must be a single int32 on the device")
+    _check(load().gaf_step(ctx.handle, _ptr(accum), _ptr(count), _ptr(g_i), g_i.numel(),
+                           _dtype_code(g_i), float(tau), _ptr(cos_dist_out), _ptr(accepted_out),
+                           _stream_handle(stream)), "gaf_step")
+
+
+def gaf_pairwise(ctx, grads, D=None, gram=None, stream=None):
+    """Enqueue the all-pairs cosine-distance matrix. Returns D (N x N float32 device tensor)."""
+    table, P, code = _grad_table(grads)
+    N = len(grads)
+    D = torch.empty((N, N), dtype=torch.float32, device=grads[0].device) if D is None else D
+    _check(load().gaf_pairwise(ctx.handle, table, N, P, code, _ptr(D), _ptr(gram),
+                               _stream_handle(stream)), "gaf_pairwise")
+    return D

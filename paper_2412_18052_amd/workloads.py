@@ -171,7 +171,7 @@ def _chunked(draw, P, device):
     return out
 
 
-def to_oracle_array(t: torch.Tensor) -> np.ndarray:
+def to_host_array(t: torch.Tensor) -> np.ndarray:
     """Host numpy view of a gradient with its exact bits: float32, or uint16
     holding the bfloat16 patterns."""
     t = t.detach().cpu().contiguous()

@@ -18,7 +18,7 @@ MARGIN = 1e-3  # every tested distance stays at least this far from tau
 
 def oracle_arrays(grads):
     from paper_2412_18052_amd import workloads as wl
-    return [wl.to_oracle_array(g) for g in grads]
+    return [wl.to_host_array(g) for g in grads]
 
 
 def workload_with_margin(name, P=None, N=None, seed=0, device="cpu", max_tries=16):

@@ -220,9 +220,9 @@ def test_step_matches_aggregate(oracle):
     cnt = 0
     for i, g in enumerate(a):
         d, acc, cnt = oracle.step(s, cnt, g, f32(w.tau))
-        assert acc == mask[i] and d == dist[i]
+        assert acc == mask[i] and abs(d - dist[i]) < 1e-13   # OpenMP combines thread sums in any order
     assert cnt == c
-    np.testing.assert_array_equal(s / cnt, out)
+    np.testing.assert_allclose(s / cnt, out, rtol=1e-15)
 
 
 # ------------------------------------------------------- pairwise -----------
@@ -297,12 +297,12 @@ def test_large_and_diagnostic_expectations(oracle):
 def test_bf16_widening_is_exact(oracle):
     import torch
     t = torch.randn(4099, generator=torch.Generator().manual_seed(7)).to(torch.bfloat16)
-    u = wl.to_oracle_array(t)
+    u = wl.to_host_array(t)
     assert u.dtype == np.uint16
     ref = t.to(torch.float64).numpy()
     out, mask, dist, c = oracle.aggregate([u], 1.0)
     np.testing.assert_array_equal(out, ref)
-    v = wl.to_oracle_array((t * 3).to(torch.bfloat16))
+    v = wl.to_host_array((t * 3).to(torch.bfloat16))
     x, y = ref, (t * 3).to(torch.bfloat16).to(torch.float64).numpy()
     d = 1 - (x @ y) / (np.linalg.norm(x) * np.linalg.norm(y))
     assert abs(oracle.cosine_distance(u, v) - d) < 1e-13
