@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the GAF filter-and-average hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One "step" is one pass of the whole hot path over one batch of synthetic
+micro-gradients already resident in HBM: a full gaf_aggregate (batch
+workloads), N gaf_step calls (streaming), or gaf_pairwise followed by
+gaf_aggregate (diagnostic). Prints ONE JSON line.
+
+value = effective HBM GB/s = (bytes the method itself must move) / time:
+    per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted (write it),
+    once per batch        s*P + 4*P for the seed,
+    pairwise              N*s*P (every gradient read once).
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
+PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+def source_digest():
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2412_18052_amd", "csrc")
+    for fn in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, fn), "rb") as fh:
+            h.update(fn.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
+def bmin_bytes(w, mask):
+    s, P = w.elem_bytes, w.P
+    total = s * P + 4 * P
+    for i in range(1, w.N):
+        total += s * P + 4 * P + (4 * P if mask[i] else 0)
+    if w.mode == "pairwise":
+        total += w.N * s * P
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large",
+                    choices=["tiny", "resnet18", "streaming", "large", "diagnostic"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--P", type=int, default=None, help="override the vector length")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the oracle baseline sample (0 disables it)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2412_18052_amd import gaf
+    from paper_2412_18052_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    torch.cuda.set_device(0)
+    gaf.load()
+
+    t0 = time.time()
+    w, grads = wl.generate(args.workload, args.seed, P=args.P, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    P, N, s = w.P, w.N, w.elem_bytes
+    ctx = gaf.gaf_create(max_P=P, max_N=max(N, 64))
+
+    out = torch.empty(P, dtype=torch.float32, device="cuda")
+    mask = torch.empty(N, dtype=torch.uint8, device="cuda")
+    dist = torch.empty(N, dtype=torch.float32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    D = torch.empty((N, N), dtype=torch.float32, device="cuda") if w.mode == "pairwise" else None
+
+    def step():
+        if w.mode == "step":
+            count.zero_()
+            for i, g in enumerate(grads):
+                gaf.gaf_step(ctx, out, count, g, w.tau, dist[i:i + 1], mask[i:i + 1])
+        else:
+            if w.mode == "pairwise":
+                gaf.gaf_pairwise(ctx, grads, D=D)
+            gaf.gaf_aggregate(ctx, grads, w.tau, out, mask, dist, count)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall_s / args.steps
+    ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
+
+    mask_h = mask.cpu().numpy().tolist()
+    dist_h = dist.cpu().numpy().tolist()
+    c_h = int(count.item())
+    step_bytes = bmin_bytes(w, mask_h)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations over the same steps, HIP events on the launch stream ----
+    gaf.gaf_profile_begin(ctx, 65536)
+    for _ in range(args.steps):
+        step()
+    times = gaf.gaf_profile_end(ctx, 65536)
+    per_kernel = {}
+    for name, ms in times:
+        per_kernel.setdefault(name, []).append(ms)
+    launches_per_step = len(times) // args.steps
+    if w.mode == "pairwise":
+        dom = "gram"
+        dur = per_kernel["gram"]
+        alg_bytes = float(N * s * P)
+        flops = 2.0 * 3 * 32 * 32 * P          # three 32x32 tiles, one multiply-add per entry per element
+        avg_ms = sum(dur) / len(dur)
+        hbm_frac = alg_bytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS
+        mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS
+        if mfma_frac >= hbm_frac:
+            roof = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12,
+                    "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac}
+        else:
+            roof = {"bound": "hbm", "achieved": alg_bytes / (avg_ms * 1e-3) / 1e9,
+                    "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": hbm_frac}
+        roof["hbm_frac"] = hbm_frac
+        roof["mfma_frac"] = mfma_frac
+    else:
+        dom = "reduce"
+        # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
+        # gradient i - 1 if that one was accepted; a streaming reduce never stores.
+        if w.mode == "step":
+            per_launch = [(4 + s) * P] * (N - 1)
+        else:
+            per_launch = [(4 + s) * P + (4 * P if mask_h[i - 1] else 0) for i in range(2, N)]
+        dur = per_kernel.get("reduce", [])
+        n_per_step = len(per_launch)
+        alg = sum(per_launch) * args.steps
+        assert len(dur) == n_per_step * args.steps, (len(dur), n_per_step, args.steps)
+        avg_ms = sum(dur) / max(1, len(dur))
+        alg_bytes = alg / max(1, len(dur))
+        ach = alg_bytes / (avg_ms * 1e-3) / 1e9 if dur else 0.0
+        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBPS}
+    roof["kernel"] = dom
+    roof["avg_launch_ms"] = avg_ms
+    roof["algorithmic_bytes_per_launch"] = alg_bytes
+    roof["traffic"] = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            tj = json.load(fh)
+        ent = tj.get("%s/%s" % (w.name, dom))
+        if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
+            roof["traffic"] = ent["hbm_bytes_per_launch"]
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle import gaf_oracle
+        cores = gaf_oracle.num_threads()
+        # sample: all N micro-gradients, the first Ps coordinates of each
+        rate_guess = 1.2e8 * cores          # element visits per second, refined by a probe
+        probe = min(P, 1 << 20)
+        host = [wl.to_host_array(g[:probe]) for g in grads]
+        tp = time.perf_counter()
+        gaf_oracle.aggregate(host, np.float32(w.tau))
+        tp = time.perf_counter() - tp
+        rate_guess = max(rate_guess, N * probe / max(tp, 1e-4))
+        Ps = int(min(P, max(probe, args.cpu_seconds * rate_guess / N)))
+        if w.mode == "pairwise":
+            Ps = int(min(P, max(1 << 16, Ps // 24)))   # the pair loop costs ~N/2 more passes
+        host = [wl.to_host_array(g[:Ps]) for g in grads]
+        tc = time.perf_counter()
+        if w.mode == "pairwise":
+            gaf_oracle.pairwise(host)
+        if w.mode == "step":
+            acc64 = np.empty(Ps, dtype=np.float64)
+            cnt, o_mask = 0, []
+            for h in host:
+                _, a_i, cnt = gaf_oracle.step(acc64, cnt, h, np.float32(w.tau))
+                o_mask.append(a_i)
+        else:
+            _, o_mask, _, _ = gaf_oracle.aggregate(host, np.float32(w.tau))
+        tc = time.perf_counter() - tc
+        ws = wl.spec(w.name, args.seed, P=Ps, N=N)
+        cpu_bytes = bmin_bytes(ws, list(o_mask))
+        cpu = {"value": cpu_bytes / tc / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+               "seconds": tc, "micro_gradients_per_s": N / tc * (Ps / P),
+               "sample": "all %d micro-gradients, first %d of %d coordinates each "
+                         "(%.3g of the workload); micro_gradients_per_s is scaled to full length"
+                         % (N, Ps, P, Ps / P)}
+
+    line = {
+        "metric": "gaf_filter_average_effective_hbm_gbps",
+        "value": value,
+        "unit": "GB/s",
+        "pct_of_hbm_peak": 100.0 * value / PEAK_HBM_GBPS,
+        "micro_gradients_per_s": N / (ms_per_step * 1e-3),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "ms_per_step_hip_events": ms_per_step_events,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "dtype_detail": "%s gradients, binary32 running mean and output, binary64 inner products"
+                        % w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau,
+                   "mode": w.mode, "seed": args.seed, "accepted": c_h,
+                   "algorithmic_bytes_per_step": step_bytes,
+                   "launches_per_step": launches_per_step, "generate_seconds": gen_s},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernel_ms": {k: sum(v) / len(v) for k, v in per_kernel.items()},
+        "accept_mask": mask_h,
+        "cos_dist": [round(x, 6) for x in dist_h],
+        "paper_reference": "no throughput reported; experiments ran on 2x NVIDIA A40 with k = 2",
+    }
+    print(json.dumps(line))
+    gaf.gaf_destroy(ctx)
+
+
+if __name__ == "__main__":
+    main()

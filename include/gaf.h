@@ -65,7 +65,7 @@ typedef enum {
     GAF_EALIGN = 2,       /* a DEVICE vector pointer is not 16-byte aligned */
     GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace */
     GAF_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
-    GAF_EUNSUPPORTED = 5, /* unknown dtype, or device is not the context's */
+    GAF_EUNSUPPORTED = 5, /* unknown dtype */
     GAF_EDEVICE = 6       /* the context's device is not the calling thread's current device */
 } gaf_status;
 
@@ -131,9 +131,8 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *   cos_dist_out  DEVICE, one binary32, may be NULL: D_i.
  *   accepted_out  DEVICE, one byte, may be NULL: 1 if accepted.
  *
- * Two kernels: the distance reduction with the decision taken by the last
- * block to finish, then the conditional update, which exits at once when g_i
- * was rejected.
+ * Three kernels: the distance reduction, a one-workgroup decision kernel, then
+ * the conditional update, which exits at once when g_i was rejected.
  */
 gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                     gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
@@ -153,6 +152,35 @@ gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i,
  */
 gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
                         float *D, double *gram, void *stream);
+
+/*
+ * Launch timing, for benchmarks (not part of the paper's method). Between
+ * gaf_profile_begin and gaf_profile_end every kernel the context enqueues is
+ * bracketed by a pair of HIP events on the call's stream (up to max_launches
+ * launches; later ones go untimed). gaf_profile_end waits for those events --
+ * the only call besides gaf_create that blocks -- and writes one record per
+ * timed launch, in launch order, into the HOST array `out` (capacity `cap`);
+ * *n (HOST) receives how many. Event objects are host resources; no device
+ * memory is allocated.
+ */
+typedef enum {
+    GAF_K_INIT = 0,          /* one-thread set-up for N == 1 */
+    GAF_K_SEED_REDUCE = 1,   /* first pass of a batch: adopt the seed, reduce against g_2 */
+    GAF_K_REDUCE = 2,        /* reduce against g_i, applying the pending update on the way */
+    GAF_K_UPDATE = 3,        /* conditional update alone */
+    GAF_K_GRAM = 4,          /* all-pairs inner products */
+    GAF_K_GRAM_FINALIZE = 5, /* ordered sum of the per-workgroup Gram tiles */
+    GAF_K_DISTANCE = 6,      /* Gram matrix -> distance matrix */
+    GAF_K_DECIDE = 7         /* ordered sum of the partial sums, distance, accept/reject decision */
+} gaf_kernel_id;
+
+typedef struct {
+    int32_t kernel; /* gaf_kernel_id */
+    float ms;       /* elapsed time between the bracketing events, milliseconds */
+} gaf_launch_time;
+
+gaf_status gaf_profile_begin(gaf_ctx *ctx, int max_launches);
+gaf_status gaf_profile_end(gaf_ctx *ctx, gaf_launch_time *out, int cap, int *n);
 
 #ifdef __cplusplus
 }

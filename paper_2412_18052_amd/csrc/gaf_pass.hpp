@@ -4,9 +4,13 @@
 // new value m of the running mean, (optionally) stores it, and (optionally)
 // accumulates the three sums of Eq. 4 against the next gradient n:
 //     dot += m*n,  nn_g += m*m,  nn_i += n*n            (binary64 accumulators)
-// The last workgroup to finish adds the per-workgroup partial sums in index
-// order, forms the distance, compares it with tau and leaves the decision in
-// device memory for the following pass. Nothing returns to the host.
+// Each workgroup leaves its three partial sums in device memory; a one-workgroup
+// kernel launched right behind adds them in index order, forms the distance,
+// compares it with tau and leaves the decision in device memory for the
+// following pass. Nothing returns to the host. (Electing the last workgroup
+// with a ticket inside the reducing kernel was measured first: the device-scope
+// fences it needs cost about 75 ns per workgroup, serialised -- 100 us per pass
+// at 1370 workgroups -- against about 3 us for the extra launch.)
 #pragma once
 #include "gaf_device.hpp"
 
@@ -57,7 +61,7 @@ __device__ __forceinline__ void element(float a, float g, float n, float inv_c, 
 // The walk over the vectors, shared by all passes. Tiles are handed to
 // workgroups round-robin so that the workgroups running at any moment read one
 // contiguous window of memory.
-template <typename T, int kMode, bool kReduce>
+template <typename T, int kMode, bool kReduce, bool kStream>
 __device__ __forceinline__ void walk(const PassArgs &a, float inv_c, double &dot, double &nn_g,
                                      double &nn_i)
 {
@@ -77,8 +81,8 @@ __device__ __forceinline__ void walk(const PassArgs &a, float inv_c, double &dot
             for (int u = 0; u < kUnroll; ++u) {
                 const size_t idx = base + size_t(u) * kBlock * 4;
                 va[u] = (kMode != kAdopt) ? load4(acc, idx) : zero4;
-                vg[u] = (kMode != kKeep) ? load4(pend, idx) : zero4;
-                vn[u] = kReduce ? load4(next, idx) : zero4;
+                vg[u] = (kMode != kKeep) ? load4<kStream>(pend, idx) : zero4;
+                vn[u] = kReduce ? load4<kStream>(next, idx) : zero4;
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -120,29 +124,39 @@ __device__ __forceinline__ void walk(const PassArgs &a, float inv_c, double &dot
     }
 }
 
-// Publishes this workgroup's sums; the workgroup that arrives last combines
-// all of them in index order, takes the decision (Algorithm 1: accept iff
-// D <= tau) and rearms the ticket. Integer ticket + fences only: no
-// floating-point atomics, so the result does not depend on arrival order.
-__device__ __forceinline__ void finish_reduction(const PassArgs &a, int32_t c_prev, double dot,
-                                                 double nn_g, double nn_i)
+// Leaves this workgroup's sums in its slot of the partial-sum table.
+__device__ __forceinline__ void publish_partials(const PassArgs &a, double dot, double nn_g,
+                                                 double nn_i)
 {
-    __shared__ int is_last;
-    const int nb = gridDim.x;
     block_sum3(dot, nn_g, nn_i);
     if (threadIdx.x == 0) {
         a.partials[0 * kMaxBlocks + blockIdx.x] = dot;
         a.partials[1 * kMaxBlocks + blockIdx.x] = nn_g;
         a.partials[2 * kMaxBlocks + blockIdx.x] = nn_i;
-        __threadfence();  // release: partials visible device-wide before the ticket moves
-        const uint32_t t = __hip_atomic_fetch_add(&a.st->ticket, 1u, __ATOMIC_ACQ_REL,
-                                                  __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (t == uint32_t(nb - 1));
     }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();  // acquire: see every other workgroup's partials
+}
 
+// One workgroup: adds the nb partial sums of the reducing pass that has just
+// finished in index order (strided per thread, then the fixed wavefront and
+// workgroup trees), forms the distance of Eq. 4 and takes the decision of
+// Algorithm 1 (accept iff D <= tau; NaN compares false). No floating-point
+// atomics anywhere, so the result does not depend on scheduling.
+// Streaming use: *count_in == 0 means the gradient is the seed and no reduction
+// was run for it.
+__global__ __launch_bounds__(kBlock) void decide_kernel(PassArgs a, int nb)
+{
+    const int32_t c_prev = a.count_in ? *a.count_in : 1;
+    State *st = a.st;
+    if (c_prev == 0) {
+        if (threadIdx.x == 0) {
+            st->accept = 1;
+            st->count = 1;
+            st->seed = 1;
+            if (a.cos_out) a.cos_out[0] = 0.f;
+            if (a.mask_out) a.mask_out[0] = 1;
+        }
+        return;
+    }
     double s0 = 0.0, s1 = 0.0, s2 = 0.0;
     for (int b = threadIdx.x; b < nb; b += kBlock) {
         s0 += a.partials[0 * kMaxBlocks + b];
@@ -153,14 +167,12 @@ __device__ __forceinline__ void finish_reduction(const PassArgs &a, int32_t c_pr
     if (threadIdx.x == 0) {
         const double D = distance_from_sums(s0, s1, s2);
         const int accept = (D <= (double)a.tau) ? 1 : 0;   // false for NaN
-        State *st = a.st;
         st->accept = accept;
         st->count = c_prev + accept;
         st->seed = 0;
         st->dot = s0;
         st->nn_g = s1;
         st->nn_i = s2;
-        st->ticket = 0;
         if (a.cos_out) a.cos_out[0] = (float)D;
         if (a.mask_out) a.mask_out[0] = (uint8_t)accept;
         if (a.count_out) a.count_out[0] = c_prev + accept;
@@ -171,14 +183,18 @@ __device__ __forceinline__ void finish_reduction(const PassArgs &a, int32_t c_pr
     }
 }
 
+// In all pass kernels kStream selects nontemporal loads for the gradient
+// streams (the aggregate itself is always loaded normally: it is about to be
+// rewritten or re-read).
+//
 // First pass of a batch: the seed g_1 becomes the aggregate (stored widened to
 // binary32) while the sums for g_2 are taken in the same walk.
-template <typename T>
+template <typename T, bool kStream>
 __global__ __launch_bounds__(kBlock) void seed_reduce_kernel(PassArgs a)
 {
     double dot = 0.0, nn_g = 0.0, nn_i = 0.0;
-    walk<T, kAdopt, true>(a, 0.f, dot, nn_g, nn_i);
-    finish_reduction(a, 1, dot, nn_g, nn_i);
+    walk<T, kAdopt, true, kStream>(a, 0.f, dot, nn_g, nn_i);
+    publish_partials(a, dot, nn_g, nn_i);
 }
 
 // Reducing pass. If a pending accepted gradient exists (a.pend non-null and the
@@ -186,33 +202,23 @@ __global__ __launch_bounds__(kBlock) void seed_reduce_kernel(PassArgs a)
 // on the way; the sums are taken on the updated aggregate.
 // Streaming use passes count_in = the caller's counter: zero there means the
 // incoming gradient is the seed, so there is nothing to compare it with.
-template <typename T>
+template <typename T, bool kStream>
 __global__ __launch_bounds__(kBlock) void reduce_kernel(PassArgs a)
 {
     const int32_t c_prev = a.count_in ? *a.count_in : 1;
-    if (c_prev == 0) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            State *st = a.st;
-            st->accept = 1;
-            st->count = 1;
-            st->seed = 1;
-            if (a.cos_out) a.cos_out[0] = 0.f;
-            if (a.mask_out) a.mask_out[0] = 1;
-        }
-        return;
-    }
+    if (c_prev == 0) return;   // seed: the decision kernel sets the state up
     const bool apply = (a.pend != nullptr) && (a.st->accept != 0);
     double dot = 0.0, nn_g = 0.0, nn_i = 0.0;
     if (apply)
-        walk<T, kUpdate, true>(a, 1.0f / (float)c_prev, dot, nn_g, nn_i);
+        walk<T, kUpdate, true, kStream>(a, 1.0f / (float)c_prev, dot, nn_g, nn_i);
     else
-        walk<T, kKeep, true>(a, 0.f, dot, nn_g, nn_i);
-    finish_reduction(a, c_prev, dot, nn_g, nn_i);
+        walk<T, kKeep, true, kStream>(a, 0.f, dot, nn_g, nn_i);
+    publish_partials(a, dot, nn_g, nn_i);
 }
 
 // Non-reducing pass: applies the pending decision and nothing else. A rejected
 // gradient costs no memory traffic (every workgroup leaves at once).
-template <typename T>
+template <typename T, bool kStream>
 __global__ __launch_bounds__(kBlock) void update_kernel(PassArgs a)
 {
     const State *st = a.st;
@@ -221,9 +227,9 @@ __global__ __launch_bounds__(kBlock) void update_kernel(PassArgs a)
     if (!accept) return;
     double d0 = 0.0, d1 = 0.0, d2 = 0.0;
     if (seed)
-        walk<T, kAdopt, false>(a, 0.f, d0, d1, d2);
+        walk<T, kAdopt, false, kStream>(a, 0.f, d0, d1, d2);
     else
-        walk<T, kUpdate, false>(a, 1.0f / (float)c, d0, d1, d2);
+        walk<T, kUpdate, false, kStream>(a, 1.0f / (float)c, d0, d1, d2);
 }
 
 // One-thread set-up for a batch of a single gradient (N == 1): the seed is the result.

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <new>
+#include <vector>
 
 #include "../../include/gaf.h"
 #include "gaf_gram.hpp"
@@ -20,6 +21,11 @@ struct gaf_ctx {
     double *partials;    // device, [3][kMaxBlocks]
     double *gram_ws;     // device, [kGramBlocks][3][kGramTile]
     double *gram_full;   // device, [max_N][max_N]
+    // launch timing (off unless gaf_profile_begin was called)
+    bool prof_on;
+    int prof_cap;
+    std::vector<hipEvent_t> prof_ev;   // start/stop pairs
+    std::vector<int32_t> prof_id;
 };
 
 namespace {
@@ -49,7 +55,41 @@ inline gaf_status launched()
     return hipGetLastError() == hipSuccess ? GAF_OK : GAF_EHIP;
 }
 
-template <typename T>
+// Brackets one kernel launch with a pair of events when launch timing is on.
+struct Timed {
+    gaf_ctx *ctx;
+    hipStream_t s;
+    bool live;
+    Timed(gaf_ctx *c, hipStream_t st, gaf_kernel_id id) : ctx(c), s(st), live(false)
+    {
+        if (!c->prof_on || static_cast<int>(c->prof_id.size()) >= c->prof_cap) return;
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess) return;
+        if (hipEventCreate(&b) != hipSuccess) {
+            (void)hipEventDestroy(a);
+            return;
+        }
+        c->prof_ev.push_back(a);
+        c->prof_ev.push_back(b);
+        c->prof_id.push_back(static_cast<int32_t>(id));
+        (void)hipEventRecord(a, s);
+        live = true;
+    }
+    ~Timed()
+    {
+        if (live) (void)hipEventRecord(ctx->prof_ev.back(), s);
+    }
+};
+
+// Gradient streams are loaded nontemporally when one pass touches more than the
+// last-level cache can hold (256 MiB on MI355X); below that, later passes find
+// the gradients still cached and the hint would throw that away.
+inline bool stream_loads(size_t P, size_t elem_bytes)
+{
+    return (4 + 2 * elem_bytes) * P > (size_t(256) << 20);
+}
+
+template <typename T, bool kStream>
 gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
                           float *out, uint8_t *mask, float *cos_dist, int32_t *count,
                           hipStream_t s)
@@ -63,11 +103,17 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
     a.dst = out;
 
     if (N == 1) {
-        init_single_kernel<<<1, 1, 0, s>>>(ctx->st, cos_dist, mask);
+        {
+            Timed t(ctx, s, GAF_K_INIT);
+            init_single_kernel<<<1, 1, 0, s>>>(ctx->st, cos_dist, mask);
+        }
         if (launched() != GAF_OK) return GAF_EHIP;
         a.pend = grads[0];
         a.count_out = count;
-        update_kernel<T><<<grid, block, 0, s>>>(a);
+        {
+            Timed t(ctx, s, GAF_K_UPDATE);
+            update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+        }
         return launched();
     }
 
@@ -78,7 +124,15 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
     a.mask_out = mask + 1;
     a.count_out = count;
     a.seed_outputs = 1;
-    seed_reduce_kernel<T><<<grid, block, 0, s>>>(a);
+    {
+        Timed t(ctx, s, GAF_K_SEED_REDUCE);
+        seed_reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    {
+        Timed t(ctx, s, GAF_K_DECIDE);
+        decide_kernel<<<1, block, 0, s>>>(a, grid.x);
+    }
     if (launched() != GAF_OK) return GAF_EHIP;
 
     // passes 2..N-1: apply the decision on grads[i-1] while reducing against grads[i]
@@ -90,7 +144,15 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
         a.next = grads[i];
         a.cos_out = cos_dist + i;
         a.mask_out = mask + i;
-        reduce_kernel<T><<<grid, block, 0, s>>>(a);
+        {
+            Timed t(ctx, s, GAF_K_REDUCE);
+            reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+        }
+        if (launched() != GAF_OK) return GAF_EHIP;
+        {
+            Timed t(ctx, s, GAF_K_DECIDE);
+            decide_kernel<<<1, block, 0, s>>>(a, grid.x);
+        }
         if (launched() != GAF_OK) return GAF_EHIP;
     }
 
@@ -100,11 +162,14 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
     a.cos_out = nullptr;
     a.mask_out = nullptr;
     a.count_out = nullptr;
-    update_kernel<T><<<grid, block, 0, s>>>(a);
+    {
+        Timed t(ctx, s, GAF_K_UPDATE);
+        update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+    }
     return launched();
 }
 
-template <typename T>
+template <typename T, bool kStream>
 gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                      float tau, float *cos_out, uint8_t *acc_out, hipStream_t s)
 {
@@ -120,7 +185,15 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
     a.count_in = count;
     a.cos_out = cos_out;
     a.mask_out = acc_out;
-    reduce_kernel<T><<<grid, block, 0, s>>>(a);
+    {
+        Timed t(ctx, s, GAF_K_REDUCE);
+        reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    {
+        Timed t(ctx, s, GAF_K_DECIDE);
+        decide_kernel<<<1, block, 0, s>>>(a, grid.x);
+    }
     if (launched() != GAF_OK) return GAF_EHIP;
     a.pend = g_i;
     a.next = nullptr;
@@ -128,7 +201,10 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
     a.cos_out = nullptr;
     a.mask_out = nullptr;
     a.count_out = count;
-    update_kernel<T><<<grid, block, 0, s>>>(a);
+    {
+        Timed t(ctx, s, GAF_K_UPDATE);
+        update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+    }
     return launched();
 }
 
@@ -150,7 +226,10 @@ gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P
         g.do_ab = ab;
         g.do_bb = bb;
         g.use_b = gb >= 0;
-        gram_kernel<T><<<kGramBlocks, kBlock, 0, s>>>(g);
+        {
+            Timed t(ctx, s, GAF_K_GRAM);
+            gram_kernel<T><<<kGramBlocks, kBlock, 0, s>>>(g);
+        }
         if (launched() != GAF_OK) return GAF_EHIP;
         GramFinalArgs f{};
         f.ws = ctx->gram_ws;
@@ -162,7 +241,10 @@ gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P
         f.do_aa = aa;
         f.do_ab = ab;
         f.do_bb = bb;
-        gram_finalize_kernel<<<(3 * kGramTile + kBlock - 1) / kBlock, kBlock, 0, s>>>(f);
+        {
+            Timed t(ctx, s, GAF_K_GRAM_FINALIZE);
+            gram_finalize_kernel<<<(3 * kGramTile + kBlock - 1) / kBlock, kBlock, 0, s>>>(f);
+        }
         return launched();
     };
     // panels of two groups: diagonal tiles and the tile between the panel's groups
@@ -179,8 +261,11 @@ gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P
             if (rc != GAF_OK) return rc;
         }
     const int n2 = N * N;
-    gram_to_distance_kernel<<<(n2 + kBlock - 1) / kBlock, kBlock, 0, s>>>(ctx->gram_full, N, D,
-                                                                         gram_out);
+    {
+        Timed t(ctx, s, GAF_K_DISTANCE);
+        gram_to_distance_kernel<<<(n2 + kBlock - 1) / kBlock, kBlock, 0, s>>>(ctx->gram_full, N, D,
+                                                                             gram_out);
+    }
     return launched();
 }
 
@@ -221,6 +306,8 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->device = device;
     ctx->max_P = max_P;
     ctx->max_N = max_N;
+    ctx->prof_on = false;
+    ctx->prof_cap = 0;
     const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * 3 * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
     bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
@@ -251,9 +338,47 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->partials) (void)hipFree(ctx->partials);
     if (ctx->gram_ws) (void)hipFree(ctx->gram_ws);
     if (ctx->gram_full) (void)hipFree(ctx->gram_full);
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;
     return GAF_OK;
+}
+
+gaf_status gaf_profile_begin(gaf_ctx *ctx, int max_launches)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (max_launches < 1) return GAF_EINVAL;
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    ctx->prof_ev.clear();
+    ctx->prof_id.clear();
+    ctx->prof_cap = max_launches;
+    ctx->prof_on = true;
+    return GAF_OK;
+}
+
+gaf_status gaf_profile_end(gaf_ctx *ctx, gaf_launch_time *out, int cap, int *n)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!out || !n || cap < 0) return GAF_EINVAL;
+    ctx->prof_on = false;
+    const int have = static_cast<int>(ctx->prof_id.size());
+    const int take = have < cap ? have : cap;
+    rc = GAF_OK;
+    for (int k = 0; k < take; ++k) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ctx->prof_ev[2 * k + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, ctx->prof_ev[2 * k], ctx->prof_ev[2 * k + 1]) != hipSuccess)
+            rc = GAF_EHIP;
+        out[k].kernel = ctx->prof_id[k];
+        out[k].ms = ms;
+    }
+    *n = take;
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    ctx->prof_ev.clear();
+    ctx->prof_id.clear();
+    return rc;
 }
 
 gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
@@ -271,9 +396,13 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
         if (misaligned(grads[i])) return GAF_EALIGN;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return dt == GAF_F32
-               ? aggregate_impl<float>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
-               : aggregate_impl<bf16_t>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+    if (dt == GAF_F32)
+        return stream_loads(P, 4)
+                   ? aggregate_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+                   : aggregate_impl<float, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+    return stream_loads(P, 2)
+               ? aggregate_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+               : aggregate_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
 }
 
 gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
@@ -288,9 +417,13 @@ gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i,
     if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
     if (misaligned(accum) || misaligned(g_i)) return GAF_EALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    return dt == GAF_F32
-               ? step_impl<float>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
-               : step_impl<bf16_t>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+    if (dt == GAF_F32)
+        return stream_loads(P, 4)
+                   ? step_impl<float, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
+                   : step_impl<float, false>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+    return stream_loads(P, 2)
+               ? step_impl<bf16_t, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
+               : step_impl<bf16_t, false>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
 }
 
 gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,

@@ -15,7 +15,13 @@ LIB_PATH = os.path.join(_HERE, "libgaf.so")
 GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEVICE = range(7)
 GAF_F32, GAF_BF16 = 0, 1
 
-SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise")
+SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
+           "gaf_profile_begin", "gaf_profile_end")
+KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide")
+
+
+class LaunchTime(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("ms", ctypes.c_float)]
 
 
 class GafError(RuntimeError):
@@ -54,6 +60,10 @@ def load(path=None):
     lib.gaf_pairwise.restype = c.c_int
     lib.gaf_pairwise.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
                                  c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_profile_begin.restype = c.c_int
+    lib.gaf_profile_begin.argtypes = [c.c_void_p, c.c_int]
+    lib.gaf_profile_end.restype = c.c_int
+    lib.gaf_profile_end.argtypes = [c.c_void_p, c.POINTER(LaunchTime), c.c_int, c.POINTER(c.c_int)]
     _lib = lib
     return lib
 
@@ -172,3 +182,15 @@ def gaf_pairwise(ctx, grads, D=None, gram=None, stream=None):
     _check(load().gaf_pairwise(ctx.handle, table, N, P, code, _ptr(D), _ptr(gram),
                                _stream_handle(stream)), "gaf_pairwise")
     return D
+
+
+def gaf_profile_begin(ctx, max_launches=4096):
+    _check(load().gaf_profile_begin(ctx.handle, int(max_launches)), "gaf_profile_begin")
+
+
+def gaf_profile_end(ctx, cap=4096):
+    """Returns [(kernel_name, milliseconds), ...] in launch order (waits for the launches)."""
+    buf = (LaunchTime * cap)()
+    n = ctypes.c_int(0)
+    _check(load().gaf_profile_end(ctx.handle, buf, cap, ctypes.byref(n)), "gaf_profile_end")
+    return [(KERNEL_NAMES[buf[k].kernel], float(buf[k].ms)) for k in range(n.value)]

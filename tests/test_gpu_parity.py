@@ -307,3 +307,71 @@ def test_argument_errors(ctx):
     torch.cuda.synchronize()
     with pytest.raises(gaf.GafError):
         gaf.gaf_aggregate(ctx, [x[1:P + 1], x[1:P + 1]], 1.0)
+
+
+# ---------------------------------------------- full-size configurations ------
+# Generated on the device (the host copy of each gradient is handed to the
+# oracle one at a time, so the host never holds the whole batch).
+def _oracle_sequential_from_device(oracle, grads, tau):
+    P = grads[0].numel()
+    g_sum = np.empty(P, dtype=np.float64)
+    cnt, mask, dist = 0, [], []
+    for g in grads:
+        d, a, cnt = oracle.step(g_sum, cnt, wl.to_host_array(g), np.float32(tau))
+        mask.append(a); dist.append(d)
+    g_sum /= cnt
+    return g_sum, np.array(mask, dtype=np.uint8), np.array(dist), cnt
+
+
+@pytest.mark.timeout(600)
+def test_large_full_size(ctx, oracle):
+    for seed in range(4):
+        w, grads = wl.generate("large", seed, device="cuda")
+        assert w.P == 1_000_000_000 and w.N == 16 and grads[0].dtype == torch.bfloat16
+        res = gaf.gaf_aggregate(ctx, grads, w.tau)
+        torch.cuda.synchronize()
+        ref = _oracle_sequential_from_device(oracle, grads, w.tau)
+        if np.all(np.abs(ref[2][1:] - np.float32(w.tau)) >= MARGIN):
+            break
+        del grads, res
+    check_against_oracle(res, ref, "bf16")
+    # the streaming entry point at the same size, on a prefix of the sequence
+    accum = torch.empty(w.P, device="cuda"); count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dist = torch.empty(6, device="cuda"); mask = torch.empty(6, dtype=torch.uint8, device="cuda")
+    for i in range(6):
+        gaf.gaf_step(ctx, accum, count, grads[i], w.tau, dist[i:i + 1], mask[i:i + 1])
+    torch.cuda.synchronize()
+    assert mask.cpu().numpy().tolist() == ref[1][:6].tolist()
+    assert np.max(np.abs(dist.cpu().numpy().astype(np.float64) - ref[2][:6])) <= DIST_ATOL
+
+
+@pytest.mark.timeout(600)
+def test_diagnostic_full_size(ctx, oracle):
+    for seed in range(4):
+        w, grads = wl.generate("diagnostic", seed, device="cuda")
+        assert w.P == 124_439_808 and w.N == 64
+        res = gaf.gaf_aggregate(ctx, grads, w.tau)
+        torch.cuda.synchronize()
+        ref = _oracle_sequential_from_device(oracle, grads, w.tau)
+        if np.all(np.abs(ref[2][1:] - np.float32(w.tau)) >= MARGIN):
+            break
+        del grads, res
+    check_against_oracle(res, ref, "f32")
+    assert ref[1].tolist() == [1 if k == 0 else 0 for k in w.cluster]
+    D = gaf.gaf_pairwise(ctx, grads)
+    torch.cuda.synchronize()
+    Dh = D.cpu().numpy().astype(np.float64)
+    assert np.array_equal(Dh, Dh.T) and np.all(np.diag(Dh) == 0)
+    assert Dh.min() >= 0 and Dh.max() <= 2
+    # sampled entries, one oracle evaluation of Eq. 4 each: all four tile kinds, far corners
+    pairs = [(0, 1), (0, 31), (0, 32), (0, 63), (31, 32), (5, 40), (17, 18), (33, 62), (62, 63),
+             (2, 0), (47, 16), (63, 31), (20, 52), (12, 44)]
+    host = {}
+    for i, j in pairs:
+        for k in (i, j):
+            if k not in host:
+                host[k] = wl.to_host_array(grads[k])
+        assert abs(Dh[i, j] - oracle.cosine_distance(host[i], host[j])) <= DIST_ATOL, (i, j)
+    # row 0 against the sequential distances up to the first acceptance
+    first = int(np.argmax(ref[1][1:])) + 1
+    assert np.max(np.abs(Dh[0, 1:first + 1] - ref[2][1:first + 1])) <= DIST_ATOL
