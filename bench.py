@@ -56,6 +56,10 @@ def main():
                     choices=["tiny", "resnet18", "streaming", "large", "diagnostic"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--P", type=int, default=None, help="override the vector length")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
+                    help="before anything else run one plain copy of ELEMS binary32 elements through "
+                         "the library (a single-gradient batch: reads 4*ELEMS bytes, writes 4*ELEMS): "
+                         "the known-size dispatch that profiler byte counters are scaled by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
     args = ap.parse_args()
@@ -72,6 +76,14 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
     gaf.load()
+
+    if args.calibrate_copy > 0:
+        cal_ctx = gaf.gaf_create(max_P=args.calibrate_copy, max_N=1)
+        src = torch.ones(args.calibrate_copy, dtype=torch.float32, device="cuda")
+        gaf.gaf_aggregate(cal_ctx, [src], 1.0)
+        torch.cuda.synchronize()
+        gaf.gaf_destroy(cal_ctx)
+        del src
 
     t0 = time.time()
     w, grads = wl.generate(args.workload, args.seed, P=args.P, device="cuda")
@@ -146,13 +158,15 @@ def main():
         # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
         # gradient i - 1 if that one was accepted; a streaming reduce never stores.
         if w.mode == "step":
-            per_launch = [(4 + s) * P] * (N - 1)
+            # the launch for the seed returns at once (nothing to compare with): not counted
+            per_launch = [None] + [(4 + s) * P] * (N - 1)
         else:
             per_launch = [(4 + s) * P + (4 * P if mask_h[i - 1] else 0) for i in range(2, N)]
         dur = per_kernel.get("reduce", [])
         n_per_step = len(per_launch)
-        alg = sum(per_launch) * args.steps
         assert len(dur) == n_per_step * args.steps, (len(dur), n_per_step, args.steps)
+        dur = [d for k, d in enumerate(dur) if per_launch[k % n_per_step] is not None]
+        alg = sum(b for b in per_launch if b is not None) * args.steps
         avg_ms = sum(dur) / max(1, len(dur))
         alg_bytes = alg / max(1, len(dur))
         ach = alg_bytes / (avg_ms * 1e-3) / 1e9 if dur else 0.0
