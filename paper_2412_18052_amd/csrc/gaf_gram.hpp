@@ -1,186 +1,279 @@
-// All-pairs inner products of up to 64 micro-gradients in one read of the data,
-// for the cosine-distance diagnostic (Eq. 4 over every pair; Fig. 1c/d).
+// All-pairs inner products of up to 64 micro-gradients in one read of the data
+// (Eq. 4 needs g_i . g_j for every pair; Fig. 1c/d logs the resulting distances).
 //
 // G = X X^T with X the (rows x P) matrix whose rows are the gradients. The
 // contraction runs over P, so it maps onto the matrix cores with P as the K
-// dimension: one v_mfma_f32_32x32x2_f32 multiplies a 32x2 slab of one 32-row
-// group with the 2x32 slab of another and adds into a 32x32 accumulator tile.
-// The 64 rows form two groups A and B; three tiles (AA, AB, BB) cover the
-// symmetric matrix. Both operands of the instruction want "lane l holds row
-// l%32, k = l/32", so one register loaded from memory serves as either operand.
+// dimension. Rows are taken in groups of 16; for every pair of groups (a <= b)
+// one 16x16 accumulator tile is kept per wavefront:
+//   binary32 rows: v_mfma_f32_16x16x4_f32   (lane l supplies row l%16, k = l/16)
+//   bfloat16 rows: v_mfma_f32_16x16x32_bf16 (lane l supplies row l%16, k = 8*(l/16)..+7)
+// Both operands of either instruction use the same lane layout and the sum runs
+// over all k, so a register loaded from memory serves as A or as B unchanged.
+// Four groups (64 rows) need 10 tiles; the symmetric half is never computed.
+//
+// Per wavefront step every lane reads 32 contiguous bytes of its row (two
+// 16-byte nontemporal loads), four lanes cover one 128-byte line of the row, and
+// the loads of the next step are issued before the MFMAs of the current one.
+// Tiles accumulate in binary32 inside the matrix core and are flushed every
+// kGramFlush steps into binary64 totals that live in LDS, one private region
+// per wavefront (keeping them in registers pushed the 10-tile kernel past 256
+// VGPRs, i.e. down to one wavefront per SIMD).
 #pragma once
 #include "gaf_device.hpp"
 
 namespace gaf {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
-constexpr int kGramRows = 64;          // rows per launch: two groups of 32
-constexpr int kGramStep = 32;          // P-elements consumed per wavefront step (2 lanes x 16 per row)
-constexpr int kGramFlush = 64;         // steps between binary32 -> binary64 flushes of the tiles
-constexpr int kGramBlocks = 512;       // workgroups per launch (fixed: summation order depends on it)
-constexpr int kGramTile = 32 * 32;     // entries per tile
+constexpr int kGramGroups = 4;          // row groups per launch
+constexpr int kGramRows = 16 * kGramGroups;
+constexpr int kGramFlush = 16;          // steps between binary32 -> binary64 flushes
+constexpr int kGramThreads = 128;       // 2 wavefronts per workgroup (LDS totals: 2 x 20 KB at 10 tiles)
+constexpr int kGramWaves = kGramThreads / 64;
+constexpr int kGramBlocks = 1024;       // workgroups per launch (fixed: the summation order depends on it)
+constexpr int kGramTile = 16 * 16;      // entries per tile
+constexpr int kGramMaxTiles = 10;       // 4 groups: 4 diagonal + 6 off-diagonal tiles
 
-struct GramArgs {
-    const void *rows[kGramRows];  // DEVICE pointers; NULL rows read as zero
-    size_t P;
-    double *ws;                   // [kGramBlocks][3][kGramTile] per-workgroup tiles
-    int do_aa, do_ab, do_bb;      // which tiles this launch computes
-    int use_b;                    // group B present
+// Which tiles a launch computes.
+//   kFull : every pair (a <= b) of the NG groups               -> NG (NG + 1) / 2 tiles
+//   kCross: groups {0,1} against groups {2,3} (NG must be 4)   -> 4 tiles
+enum GramMode { kFull = 0, kCross = 1 };
+
+// Tiles are numbered so that the first NG (NG + 1) / 2 of them are exactly the
+// pairs among the first NG groups: (0,0) (0,1) (1,1) (0,2) (1,2) (2,2) (0,3) ...
+template <int NG, int kMode>
+struct TileList {
+    static constexpr int count = kMode == kFull ? NG * (NG + 1) / 2 : 4;
+    // tile t -> (row group, column group)
+    __host__ __device__ static constexpr int ga(int t)
+    {
+        constexpr int full[kGramMaxTiles] = {0, 0, 1, 0, 1, 2, 0, 1, 2, 3};
+        constexpr int cross[4] = {0, 0, 1, 1};
+        return kMode == kFull ? full[t] : cross[t];
+    }
+    __host__ __device__ static constexpr int gb(int t)
+    {
+        constexpr int full[kGramMaxTiles] = {0, 1, 1, 2, 2, 2, 3, 3, 3, 3};
+        constexpr int cross[4] = {2, 3, 2, 3};
+        return kMode == kFull ? full[t] : cross[t];
+    }
 };
 
-// 16 consecutive elements of one row, widened, as four float4. p is a multiple of 16.
-__device__ __forceinline__ void load16(const float *row, size_t p, float4 (&v)[4])
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = *reinterpret_cast<const float4 *>(row + p + 4 * j);
-}
-__device__ __forceinline__ void load16(const bf16_t *row, size_t p, float4 (&v)[4])
-{
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const uint4 r = *reinterpret_cast<const uint4 *>(row + p + 8 * j);
-        v[2 * j] = make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
-                               __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
-        v[2 * j + 1] = make_float4(__uint_as_float(r.z << 16), __uint_as_float(r.z & 0xffff0000u),
-                                   __uint_as_float(r.w << 16), __uint_as_float(r.w & 0xffff0000u));
-    }
-}
-template <typename T>
-__device__ __forceinline__ void load16_guarded(const T *row, size_t p, size_t P, float4 (&v)[4])
-{
-    float e[16];
-#pragma unroll
-    for (int k = 0; k < 16; ++k) e[k] = (p + k < P) ? load1(row, p + k) : 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = make_float4(e[4 * j], e[4 * j + 1], e[4 * j + 2], e[4 * j + 3]);
-}
+struct GramArgs {
+    const void *rows[kGramRows];  // DEVICE pointers, group g = rows[16 g .. 16 g + 15]; never NULL: rows past
+                                  // the last gradient alias a real one and their tile entries are dropped
+    size_t P;
+    double *ws;                   // [kGramBlocks][kGramMaxTiles][kGramTile] per-workgroup tiles
+};
 
-__device__ __forceinline__ void mfma16(const float4 (&x)[4], const float4 (&y)[4], floatx16 &acc)
-{
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[j].x, y[j].x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[j].y, y[j].y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[j].z, y[j].z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(x[j].w, y[j].w, acc, 0, 0, 0);
-    }
-}
+// ---- one step's worth of one row for one lane: 32 bytes --------------------
+template <typename T> struct GramTraits;
+template <> struct GramTraits<float> {
+    static constexpr int kLane = 8;                 // elements per lane per step
+    typedef f32x4_t raw;
+};
+template <> struct GramTraits<bf16_t> {
+    static constexpr int kLane = 16;
+    typedef u32x4_t raw;
+};
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
+__device__ __forceinline__ void gram_load(const T *row, size_t p, typename GramTraits<T>::raw (&v)[2])
 {
-    __shared__ double tile_lds[3 * kGramTile];     // 24 KB: cross-wavefront combine
+    typedef typename GramTraits<T>::raw raw;
+    constexpr int half = GramTraits<T>::kLane / 2;
+    v[0] = __builtin_nontemporal_load(reinterpret_cast<const raw *>(row + p));
+    v[1] = __builtin_nontemporal_load(reinterpret_cast<const raw *>(row + p + half));
+}
+__device__ __forceinline__ void gram_load_guarded(const float *row, size_t p, size_t P, f32x4_t (&v)[2])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const size_t q = p + 4 * h + e;
+            v[h][e] = q < P ? row[q] : 0.f;
+        }
+}
+__device__ __forceinline__ void gram_load_guarded(const bf16_t *row, size_t p, size_t P, u32x4_t (&v)[2])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const size_t q = p + 8 * h + 2 * e;
+            const uint32_t lo = q < P ? row[q] : 0u, hi = q + 1 < P ? row[q + 1] : 0u;
+            v[h][e] = lo | (hi << 16);
+        }
+}
+
+__device__ __forceinline__ void gram_mma(const f32x4_t (&x)[2], const f32x4_t (&y)[2], floatx4 &acc, int h, int e)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x[h][e], y[h][e], acc, 0, 0, 0);
+}
+__device__ __forceinline__ void gram_mma(const u32x4_t (&x)[2], const u32x4_t (&y)[2], floatx4 &acc, int h, int)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x[h]),
+                                                  __builtin_bit_cast(bf16x8_t, y[h]), acc, 0, 0, 0);
+}
+
+template <typename T, int NG, int kMode>
+__global__ __launch_bounds__(kGramThreads) void gram_kernel(GramArgs a)
+{
+    typedef TileList<NG, kMode> Tiles;
+    typedef typename GramTraits<T>::raw raw;
+    constexpr int NT = Tiles::count;
+    constexpr int kLane = GramTraits<T>::kLane;
+    constexpr int kStep = 4 * kLane;                    // elements of each row per wavefront step (128 bytes)
+    constexpr int kInner = sizeof(T) == 4 ? 4 : 1;      // MFMAs per 16-byte register
+
+    __shared__ double tot_lds[kGramWaves][NT * kGramTile];   // per-wavefront binary64 totals, <= 40 KB
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 31, h = lane >> 5;
+    const int r = lane & 15, kq = lane >> 4;
 
-    // this lane's row of each group, picked with compile-time indices so the
+    // this lane's row in each group, selected with compile-time indices so the
     // pointer table stays in the kernel-argument segment
-    const T *row_a = nullptr, *row_b = nullptr;
+    const T *row[NG];
 #pragma unroll
-    for (int k = 0; k < 32; ++k) {
-        if (r == k) {
-            row_a = static_cast<const T *>(a.rows[k]);
-            row_b = static_cast<const T *>(a.rows[32 + k]);
-        }
+    for (int g = 0; g < NG; ++g) {
+        row[g] = nullptr;
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (r == k) row[g] = static_cast<const T *>(a.rows[16 * g + k]);
     }
-    const bool use_b = a.use_b != 0;
 
     const size_t P = a.P;
-    const size_t nsteps = (P + kGramStep - 1) / kGramStep;
-    const size_t nwaves = size_t(gridDim.x) * kWaves;
-    const size_t gw = size_t(blockIdx.x) * kWaves + wave;
+    const size_t nwaves = size_t(gridDim.x) * kGramWaves;
+    const size_t gw = size_t(blockIdx.x) * kGramWaves + wave;
 
-    floatx16 acc_aa = {0}, acc_ab = {0}, acc_bb = {0};
-    double tot_aa[16], tot_ab[16], tot_bb[16];
+    // Tile entry in accumulator register v of lane l: row i = 4*(l/16) + v, column j = l%16.
+    double *tot = &tot_lds[wave][(4 * kq) * 16 + r];   // + t*kGramTile + v*16
+    floatx4 acc[NT];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) tot_aa[v] = tot_ab[v] = tot_bb[v] = 0.0;
+    for (int t = 0; t < NT; ++t) {
+        acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) tot[t * kGramTile + v * 16] = 0.0;
+    }
 
+    // Hot-loop loads are unconditional (absent rows alias a real row on the host
+    // side and their tile entries are dropped later), so the compiler keeps all
+    // of a step's loads in flight behind one counter wait.
+    auto load_step = [&](size_t s, raw (&x)[NG][2]) {
+        const size_t p = s * kStep + size_t(kq) * kLane;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) gram_load(row[g], p, x[g]);
+    };
+    auto compute = [&](const raw (&x)[NG][2]) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int e = 0; e < kInner; ++e)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) gram_mma(x[Tiles::ga(t)], x[Tiles::gb(t)], acc[t], h, e);
+    };
+    auto flush = [&]() {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                tot[t * kGramTile + v * 16] += (double)acc[t][v];   // this lane's own LDS slot
+                acc[t][v] = 0.f;
+            }
+    };
+
+    // Full steps, two register buffers: the loads of step k+1 are in flight while
+    // step k is multiplied. The steady-state loop has no conditional loads.
+    const size_t nfull = P / kStep;
+    raw x0[NG][2], x1[NG][2];
     int since_flush = 0;
-    for (size_t s = gw; s < nsteps; s += nwaves) {
-        const size_t p = s * kGramStep + size_t(h) * 16;
-        float4 xa[4], xb[4];
-        const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) xa[j] = xb[j] = zero4;
-        if ((s + 1) * kGramStep <= P) {
-            if (row_a) load16(row_a, p, xa);
-            if (use_b && row_b) load16(row_b, p, xb);
-        } else {
-            if (row_a) load16_guarded(row_a, p, P, xa);
-            if (use_b && row_b) load16_guarded(row_b, p, P, xb);
-        }
-        if (a.do_aa) mfma16(xa, xa, acc_aa);
-        if (a.do_ab) mfma16(xa, xb, acc_ab);
-        if (a.do_bb) mfma16(xb, xb, acc_bb);
+    auto after_step = [&]() {
         if (++since_flush == kGramFlush) {
             since_flush = 0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                tot_aa[v] += (double)acc_aa[v];
-                tot_ab[v] += (double)acc_ab[v];
-                tot_bb[v] += (double)acc_bb[v];
-                acc_aa[v] = acc_ab[v] = acc_bb[v] = 0.f;
-            }
+            flush();
+        }
+    };
+    size_t s = gw;
+    if (s < nfull) {
+        load_step(s, x0);
+        while (s + 2 * nwaves < nfull) {
+            load_step(s + nwaves, x1);
+            compute(x0);
+            after_step();
+            load_step(s + 2 * nwaves, x0);
+            compute(x1);
+            after_step();
+            s += 2 * nwaves;
+        }
+        if (s + nwaves < nfull) {
+            load_step(s + nwaves, x1);
+            compute(x0);
+            compute(x1);
+        } else {
+            compute(x0);
         }
     }
+    // ragged tail (P not a multiple of the step): one wavefront, element-wise guarded loads
+    if (nfull * kStep < P && gw == nfull % nwaves) {
+        const size_t p = nfull * kStep + size_t(kq) * kLane;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        tot_aa[v] += (double)acc_aa[v];
-        tot_ab[v] += (double)acc_ab[v];
-        tot_bb[v] += (double)acc_bb[v];
+        for (int g = 0; g < NG; ++g) gram_load_guarded(row[g], p, P, x0[g]);
+        compute(x0);
     }
+    flush();
 
-    // Tile entry held in accumulator register v of lane l: row i = 8*(v/4) + 4*(l/32) + v%4,
-    // column j = l%32. Wavefronts add their tiles into LDS one after the other.
-    for (int w = 0; w < kWaves; ++w) {
-        if (wave == w) {
+    // the workgroup's tile = its wavefronts' totals added in wavefront order
+    __syncthreads();
+    double *out = a.ws + size_t(blockIdx.x) * kGramMaxTiles * kGramTile;
+    for (int e = threadIdx.x; e < NT * kGramTile; e += kGramThreads) {
+        double v = tot_lds[0][e];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int i = 8 * (v / 4) + 4 * h + (v % 4);
-                const int e = i * 32 + r;
-                if (w == 0) {
-                    tile_lds[0 * kGramTile + e] = tot_aa[v];
-                    tile_lds[1 * kGramTile + e] = tot_ab[v];
-                    tile_lds[2 * kGramTile + e] = tot_bb[v];
-                } else {
-                    tile_lds[0 * kGramTile + e] += tot_aa[v];
-                    tile_lds[1 * kGramTile + e] += tot_ab[v];
-                    tile_lds[2 * kGramTile + e] += tot_bb[v];
-                }
-            }
-        }
-        __syncthreads();
+        for (int w = 1; w < kGramWaves; ++w) v += tot_lds[w][e];
+        out[e] = v;
     }
-    double *out = a.ws + size_t(blockIdx.x) * 3 * kGramTile;
-    for (int e = threadIdx.x; e < 3 * kGramTile; e += kBlock) out[e] = tile_lds[e];
 }
 
-// Adds the per-workgroup tiles in workgroup order and scatters the three tiles
-// into the full symmetric matrix of inner products (binary64, ld = N).
+// Adds the per-workgroup tiles in workgroup order and scatters them into the
+// full symmetric matrix of inner products (binary64, leading dimension N).
 struct GramFinalArgs {
     const double *ws;
     int nblocks;
+    int ntiles;
+    int tile_ga[kGramMaxTiles], tile_gb[kGramMaxTiles];  // local group of each tile's rows / columns
+    int group_row[kGramGroups];                          // first global row of each local group
     double *gram;   // [N][N]
     int N;
-    int row_a, row_b;   // first global row of group A / group B
-    int do_aa, do_ab, do_bb;
 };
 
+// One workgroup handles 16 consecutive tile entries; thread (slice, entry) adds
+// the workgroups of its slice in order, then the 16 slice sums are added in
+// slice order: a fixed tree, so the result is reproducible.
 __global__ __launch_bounds__(kBlock) void gram_finalize_kernel(GramFinalArgs a)
 {
-    const int e = blockIdx.x * kBlock + threadIdx.x;   // 0 .. 3*1024-1
-    if (e >= 3 * kGramTile) return;
-    const int tile = e / kGramTile, i = (e % kGramTile) / 32, j = e % 32;
-    if ((tile == 0 && !a.do_aa) || (tile == 1 && !a.do_ab) || (tile == 2 && !a.do_bb)) return;
+    __shared__ double part[16][16];
+    const int el = threadIdx.x & 15, slice = threadIdx.x >> 4;
+    const int e = blockIdx.x * 16 + el;
+    const bool live = e < a.ntiles * kGramTile;
+    const int per = (a.nblocks + 15) / 16;
     double s = 0.0;
-    for (int b = 0; b < a.nblocks; ++b) s += a.ws[size_t(b) * 3 * kGramTile + e];
-    const int gi = (tile == 2 ? a.row_b : a.row_a) + i;
-    const int gj = (tile == 0 ? a.row_a : a.row_b) + j;
+    if (live) {
+        const int b1 = (slice + 1) * per < a.nblocks ? (slice + 1) * per : a.nblocks;
+        for (int b = slice * per; b < b1; ++b) s += a.ws[size_t(b) * kGramMaxTiles * kGramTile + e];
+    }
+    part[slice][el] = s;
+    __syncthreads();
+    if (slice != 0 || !live) return;
+    s = part[0][el];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) s += part[k][el];
+    const int t = e / kGramTile, i = (e % kGramTile) / 16, j = e % 16;
+    const int gi = a.group_row[a.tile_ga[t]] + i, gj = a.group_row[a.tile_gb[t]] + j;
     if (gi >= a.N || gj >= a.N) return;
     a.gram[size_t(gi) * a.N + gj] = s;
-    if (tile == 1) a.gram[size_t(gj) * a.N + gi] = s;
+    if (a.tile_ga[t] != a.tile_gb[t]) a.gram[size_t(gj) * a.N + gi] = s;
 }
 
 // Eq. 4 for every pair from the matrix of inner products.

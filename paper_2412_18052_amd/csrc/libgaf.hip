@@ -19,7 +19,7 @@ struct gaf_ctx {
     int max_N;
     State *st;           // device
     double *partials;    // device, [3][kMaxBlocks]
-    double *gram_ws;     // device, [kGramBlocks][3][kGramTile]
+    double *gram_ws;     // device, [kGramBlocks][kGramMaxTiles][kGramTile]
     double *gram_full;   // device, [max_N][max_N]
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
@@ -208,58 +208,83 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
     return launched();
 }
 
+// Enqueues the Gram kernel for up to four 16-row groups (global group indices in
+// `groups`, -1 = absent) and the ordered combine of its per-workgroup tiles into
+// ctx->gram_full (leading dimension N).
+template <typename T, int NG, int kMode>
+gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, const int (&groups)[4],
+                       hipStream_t s)
+{
+    typedef TileList<NG, kMode> Tiles;
+    GramArgs g{};
+    GramFinalArgs f{};
+    for (int k = 0; k < NG; ++k) {
+        for (int r = 0; r < 16; ++r) {
+            const int i = groups[k] * 16 + r;
+            g.rows[16 * k + r] = (groups[k] >= 0 && i < N) ? grads[i] : grads[0];   // alias: result dropped
+        }
+        f.group_row[k] = groups[k] >= 0 ? groups[k] * 16 : N;   // absent group: rows >= N are dropped
+    }
+    g.P = P;
+    g.ws = ctx->gram_ws;
+    {
+        Timed t(ctx, s, GAF_K_GRAM);
+        gram_kernel<T, NG, kMode><<<kGramBlocks, kGramThreads, 0, s>>>(g);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    f.ws = ctx->gram_ws;
+    f.nblocks = kGramBlocks;
+    f.ntiles = Tiles::count;
+    for (int t = 0; t < Tiles::count; ++t) {
+        f.tile_ga[t] = Tiles::ga(t);
+        f.tile_gb[t] = Tiles::gb(t);
+    }
+    f.gram = ctx->gram_full;
+    f.N = N;
+    {
+        Timed t(ctx, s, GAF_K_GRAM_FINALIZE);
+        gram_finalize_kernel<<<(Tiles::count * kGramTile + 15) / 16, kBlock, 0, s>>>(f);
+    }
+    return launched();
+}
+
+// Inner products of all pairs into ctx->gram_full. N <= 64: one launch, every
+// gradient read once. Larger N: 64-row panels, then the tiles between 32-row
+// halves of different panels.
+template <typename T>
+gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s)
+{
+    const int ng = (N + 15) / 16;
+    for (int g0 = 0; g0 < ng; g0 += 4) {
+        const int n = ng - g0 < 4 ? ng - g0 : 4;
+        const int groups[4] = {g0, n > 1 ? g0 + 1 : -1, n > 2 ? g0 + 2 : -1, n > 3 ? g0 + 3 : -1};
+        gaf_status rc = GAF_OK;
+        switch (n) {
+        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s); break;
+        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s); break;
+        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s); break;
+        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s); break;
+        }
+        if (rc != GAF_OK) return rc;
+    }
+    const int nh = (ng + 1) / 2;   // 32-row halves
+    for (int ha = 0; ha < nh; ++ha)
+        for (int hb = ha + 1; hb < nh; ++hb) {
+            if (ha / 2 == hb / 2) continue;   // same panel: done above
+            const int groups[4] = {2 * ha, 2 * ha + 1 < ng ? 2 * ha + 1 : -1, 2 * hb,
+                                   2 * hb + 1 < ng ? 2 * hb + 1 : -1};
+            const gaf_status rc = gram_launch<T, 4, kCross>(ctx, grads, N, P, groups, s);
+            if (rc != GAF_OK) return rc;
+        }
+    return GAF_OK;
+}
+
 template <typename T>
 gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float *D,
                          double *gram_out, hipStream_t s)
 {
-    const int ngroups = (N + 31) / 32;
-    auto launch = [&](int ga, int gb, int aa, int ab, int bb) -> gaf_status {
-        GramArgs g{};
-        for (int k = 0; k < 32; ++k) {
-            const int ia = ga * 32 + k, ib = gb * 32 + k;
-            g.rows[k] = ia < N ? grads[ia] : nullptr;
-            g.rows[32 + k] = (gb >= 0 && ib < N) ? grads[ib] : nullptr;
-        }
-        g.P = P;
-        g.ws = ctx->gram_ws;
-        g.do_aa = aa;
-        g.do_ab = ab;
-        g.do_bb = bb;
-        g.use_b = gb >= 0;
-        {
-            Timed t(ctx, s, GAF_K_GRAM);
-            gram_kernel<T><<<kGramBlocks, kBlock, 0, s>>>(g);
-        }
-        if (launched() != GAF_OK) return GAF_EHIP;
-        GramFinalArgs f{};
-        f.ws = ctx->gram_ws;
-        f.nblocks = kGramBlocks;
-        f.gram = ctx->gram_full;
-        f.N = N;
-        f.row_a = ga * 32;
-        f.row_b = gb >= 0 ? gb * 32 : 0;
-        f.do_aa = aa;
-        f.do_ab = ab;
-        f.do_bb = bb;
-        {
-            Timed t(ctx, s, GAF_K_GRAM_FINALIZE);
-            gram_finalize_kernel<<<(3 * kGramTile + kBlock - 1) / kBlock, kBlock, 0, s>>>(f);
-        }
-        return launched();
-    };
-    // panels of two groups: diagonal tiles and the tile between the panel's groups
-    for (int ga = 0; ga < ngroups; ga += 2) {
-        const bool pair = ga + 1 < ngroups;
-        const gaf_status rc = launch(ga, pair ? ga + 1 : -1, 1, pair ? 1 : 0, pair ? 1 : 0);
-        if (rc != GAF_OK) return rc;
-    }
-    // tiles between groups of different panels
-    for (int ga = 0; ga < ngroups; ++ga)
-        for (int gb = ga + 1; gb < ngroups; ++gb) {
-            if (ga / 2 == gb / 2) continue;
-            const gaf_status rc = launch(ga, gb, 0, 1, 0);
-            if (rc != GAF_OK) return rc;
-        }
+    const gaf_status rc = gram_all_pairs<T>(ctx, grads, N, P, s);
+    if (rc != GAF_OK) return rc;
     const int n2 = N * N;
     {
         Timed t(ctx, s, GAF_K_DISTANCE);
@@ -308,7 +333,7 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->max_N = max_N;
     ctx->prof_on = false;
     ctx->prof_cap = 0;
-    const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * 3 * kGramTile;
+    const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
     bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->partials),
