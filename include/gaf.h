@@ -108,13 +108,39 @@ const char *gaf_strerror(gaf_status status);
  *                [0] = 0 (the seed is not compared with anything).
  *   count        DEVICE, one int32: c, the number of accepted gradients (>= 1).
  *
- * HBM traffic per visited gradient: the aggregate is read once and g_i once
- * for the distance; an accepted g_i is read a second time, in the same pass
- * that reduces the next gradient, when the aggregate is rewritten.
+ * HBM traffic, sequential schedule, per visited gradient: the aggregate is read
+ * once and g_i once for the distance; an accepted g_i is read a second time, in
+ * the same pass that reduces the next gradient, when the aggregate is rewritten.
+ * Gram-first schedule (the default for N <= 64, see gaf_set_schedule): every
+ * gradient is read once, the accepted ones a second time, out is written once.
  */
 gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
                          float tau, float *out, uint8_t *accept_mask, float *cos_dist,
                          int32_t *count, void *stream);
+
+/*
+ * How gaf_aggregate schedules its work. Both schedules implement the same
+ * Algorithm 1 and give the same mask, count, distances and macro-gradient up
+ * to rounding.
+ *   SEQUENTIAL  one streaming pass per visited gradient: the distance of g_i to
+ *               the running aggregate, with the update for g_{i-1} fused into
+ *               the same pass (see the traffic note above).
+ *   GRAM        the decisions depend on the gradients only through inner
+ *               products (g_i . sum_A g_j = sum_{j in A} g_i . g_j, and likewise
+ *               for the norm of the running sum), so: all-pairs inner products
+ *               in ONE read of every gradient, an O(N^2) scalar replay of
+ *               Algorithm 1 on the device, then Eq. 5 as one masked mean over
+ *               the accepted gradients (c reads, one write). 2 <= N <= 64.
+ *   AUTO        GRAM when 2 <= N <= 64, otherwise SEQUENTIAL. The default.
+ * Explicit GRAM with N outside its range returns GAF_EUNSUPPORTED.
+ */
+typedef enum {
+    GAF_SCHEDULE_AUTO = 0,
+    GAF_SCHEDULE_SEQUENTIAL = 1,
+    GAF_SCHEDULE_GRAM = 2
+} gaf_schedule;
+
+gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule);
 
 /*
  * Streaming form: one visit of Algorithm 1's inner loop for a gradient that
@@ -171,7 +197,9 @@ typedef enum {
     GAF_K_GRAM = 4,          /* all-pairs inner products */
     GAF_K_GRAM_FINALIZE = 5, /* ordered sum of the per-workgroup Gram tiles */
     GAF_K_DISTANCE = 6,      /* Gram matrix -> distance matrix */
-    GAF_K_DECIDE = 7         /* ordered sum of the partial sums, distance, accept/reject decision */
+    GAF_K_DECIDE = 7,        /* ordered sum of the partial sums, distance, accept/reject decision */
+    GAF_K_FILTER = 8,        /* Gram-first schedule: Algorithm 1 replayed on the Gram matrix */
+    GAF_K_MEAN = 9           /* Gram-first schedule: mean of the accepted gradients (Eq. 5) */
 } gaf_kernel_id;
 
 typedef struct {

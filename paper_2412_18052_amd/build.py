@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgaf.so")
 SOURCES = [os.path.join(CSRC, "libgaf.hip")]
-HEADERS = [os.path.join(CSRC, h) for h in ("gaf_device.hpp", "gaf_pass.hpp", "gaf_gram.hpp")] + [
+HEADERS = [os.path.join(CSRC, h) for h in ("gaf_device.hpp", "gaf_pass.hpp", "gaf_gram.hpp", "gaf_batch.hpp")] + [
     os.path.join(os.path.dirname(HERE), "include", "gaf.h")]
 
 HIPCC_FLAGS = [

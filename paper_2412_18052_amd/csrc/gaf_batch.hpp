@@ -1,0 +1,131 @@
+// Gram-first schedule of the batch aggregation.
+//
+// The decisions of Algorithm 1 depend on the gradients only through inner
+// products. With A the set accepted before g_i is visited and G_jk = g_j . g_k:
+//     g_i . sum_A g_j = sum_{j in A} G_ij,   |sum_A g_j|^2 = sum_{j,k in A} G_jk,
+//     |g_i|^2 = G_ii,
+// so Eq. 4 for every visit, and hence the whole accept mask, follows from the
+// N x N Gram matrix. The batch then costs one read of every gradient (Gram
+// kernel), an O(N^2) scalar scan (filter_kernel below), and one read of the
+// accepted gradients plus one write of the result (mean_kernel, Eq. 5) --
+// instead of one read of the aggregate per visit and a rewrite per acceptance.
+// Same mask, distances and macro-gradient as the sequential schedule up to
+// rounding; the distances here come from exact-product binary64 sums.
+#pragma once
+#include "gaf_device.hpp"
+#include "gaf_pass.hpp"
+
+namespace gaf {
+
+constexpr int kBatchMaxN = 64;   // gradients the Gram-first schedule handles (one Gram launch)
+
+// One wavefront. Visits g_2..g_N in order exactly as Algorithm 1 does, with the
+// three sums of Eq. 4 taken from the Gram matrix. Lane k carries the k-th
+// accepted index; the dot product is a fixed-tree wavefront sum.
+__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
+                                                    uint8_t *mask, float *cos_dist, int32_t *count,
+                                                    int32_t *accepted_list)
+{
+    const int lane = threadIdx.x;
+    int my_index = lane == 0 ? 0 : -1;      // lane k < c holds the k-th accepted gradient
+    int c = 1;
+    double nn_g = gram[0];                  // |running sum|^2
+    if (lane == 0) {
+        mask[0] = 1;
+        cos_dist[0] = 0.f;
+        accepted_list[0] = 0;
+    }
+    for (int i = 1; i < N; ++i) {
+        const double term = my_index >= 0 ? gram[size_t(my_index) * N + i] : 0.0;
+        const double dot = wave_sum(term);
+        const double nn_i = gram[size_t(i) * N + i];
+        const double D = distance_from_sums(dot, nn_g, nn_i);
+        const bool accept = D <= (double)tau;      // false for NaN
+        if (lane == 0) {
+            mask[i] = accept ? 1 : 0;
+            cos_dist[i] = (float)D;
+        }
+        if (accept) {
+            if (lane == c) my_index = i;
+            if (lane == 0) accepted_list[c] = i;
+            nn_g = nn_g + 2.0 * dot + nn_i;
+            ++c;
+        }
+    }
+    if (lane == 0) {
+        count[0] = c;
+        st->count = c;
+        st->accept = 0;
+        st->seed = 0;
+    }
+}
+
+struct MeanArgs {
+    const void *rows[kBatchMaxN];   // DEVICE pointers of all N gradients
+    int N;
+    const int32_t *accepted_list;   // DEVICE, indices of the accepted gradients in visiting order
+    const State *st;                // st->count = c
+    float *out;
+    size_t P;
+};
+
+// Eq. 5: out = (sum of the accepted gradients) / c, accumulated in binary32 in
+// visiting order. Reads c gradients once, writes the result once.
+template <typename T, bool kStream>
+__global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
+{
+    __shared__ const void *table[kBatchMaxN];
+    __shared__ int32_t list[kBatchMaxN];
+    const int c = a.st->count;
+    if (threadIdx.x < kBatchMaxN) {
+        const void *p = nullptr;
+#pragma unroll
+        for (int k = 0; k < kBatchMaxN; ++k)
+            if (int(threadIdx.x) == k) p = a.rows[k];
+        table[threadIdx.x] = p;
+        list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;
+    }
+    __syncthreads();
+    const float inv_c = 1.0f / (float)c;
+    const size_t P = a.P;
+    const size_t ntiles = (P + kTile - 1) / kTile;
+    float *out = a.out;
+
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const size_t base = t * kTile + size_t(threadIdx.x) * 4;
+        if ((t + 1) * kTile <= P) {
+            float4 sum[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) sum[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < c; ++k) {
+                const T *g = static_cast<const T *>(table[list[k]]);
+                float4 v[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) v[u] = load4<kStream>(g, base + size_t(u) * kBlock * 4);
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    sum[u].x += v[u].x;
+                    sum[u].y += v[u].y;
+                    sum[u].z += v[u].z;
+                    sum[u].w += v[u].w;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                *reinterpret_cast<float4 *>(out + base + size_t(u) * kBlock * 4) =
+                    make_float4(sum[u].x * inv_c, sum[u].y * inv_c, sum[u].z * inv_c, sum[u].w * inv_c);
+        } else {
+            // ragged last tile, element-wise
+            for (int u = 0; u < kUnroll; ++u)
+                for (int e = 0; e < 4; ++e) {
+                    const size_t idx = base + size_t(u) * kBlock * 4 + e;
+                    if (idx >= P) continue;
+                    float sum = 0.f;
+                    for (int k = 0; k < c; ++k) sum += load1(static_cast<const T *>(table[list[k]]), idx);
+                    out[idx] = sum * inv_c;
+                }
+        }
+    }
+}
+
+}  // namespace gaf

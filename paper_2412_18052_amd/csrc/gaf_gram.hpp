@@ -8,16 +8,22 @@
 //   binary32 rows: v_mfma_f32_16x16x4_f32   (lane l supplies row l%16, k = l/16)
 //   bfloat16 rows: v_mfma_f32_16x16x32_bf16 (lane l supplies row l%16, k = 8*(l/16)..+7)
 // Both operands of either instruction use the same lane layout and the sum runs
-// over all k, so a register loaded from memory serves as A or as B unchanged.
-// Four groups (64 rows) need 10 tiles; the symmetric half is never computed.
+// over all k, so one register serves as A or as B unchanged. Four groups (64
+// rows) need 10 tiles; the symmetric half is never computed.
 //
-// Per wavefront step every lane reads 32 contiguous bytes of its row (two
-// 16-byte nontemporal loads), four lanes cover one 128-byte line of the row, and
-// the loads of the next step are issued before the MFMAs of the current one.
-// Tiles accumulate in binary32 inside the matrix core and are flushed every
-// kGramFlush steps into binary64 totals that live in LDS, one private region
-// per wavefront (keeping them in registers pushed the 10-tile kernel past 256
-// VGPRs, i.e. down to one wavefront per SIMD).
+// Memory side. The matrix-core layout wants 16 different rows in 16 adjacent
+// lanes. Loading global memory that way (each lane 32 bytes of its own row) was
+// measured at 2.6 TB/s with the MFMAs removed -- every 16-lane group of a load
+// touches 16 different cache lines. So global loads are made fully coalesced
+// instead (16 adjacent lanes read 256 contiguous bytes of ONE row, a wavefront
+// load covers 4 rows) and the tile of the matrix is turned through LDS:
+//   stage = (16 NG rows) x (256 M bytes); each of the 4 wavefronts loads a
+//   quarter of the rows, stores its 16-byte pieces to LDS (row stride padded by
+//   16 bytes: conflict-free), and after one barrier reads back, for EVERY row,
+//   its own quarter of the stage's columns in matrix-core layout.
+// Two LDS stages alternate; the global loads of stage k+1 are issued before the
+// MFMAs of stage k. Tiles accumulate in binary32 inside the matrix core and are
+// flushed into binary64 registers every kGramFlush stages.
 #pragma once
 #include "gaf_device.hpp"
 
@@ -29,12 +35,11 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kGramGroups = 4;          // row groups per launch
 constexpr int kGramRows = 16 * kGramGroups;
-constexpr int kGramFlush = 16;          // steps between binary32 -> binary64 flushes
-constexpr int kGramThreads = 128;       // 2 wavefronts per workgroup (LDS totals: 2 x 20 KB at 10 tiles)
-constexpr int kGramWaves = kGramThreads / 64;
-constexpr int kGramBlocks = 1024;       // workgroups per launch (fixed: the summation order depends on it)
+constexpr int kGramFlush = 8;           // stages between binary32 -> binary64 flushes
+constexpr int kGramBlocks = 512;        // workgroups per launch (fixed: the summation order depends on it)
 constexpr int kGramTile = 16 * 16;      // entries per tile
 constexpr int kGramMaxTiles = 10;       // 4 groups: 4 diagonal + 6 off-diagonal tiles
+constexpr int kGramPad = 4;             // LDS row padding, 32-bit words
 
 // Which tiles a launch computes.
 //   kFull : every pair (a <= b) of the NG groups               -> NG (NG + 1) / 2 tiles
@@ -61,6 +66,10 @@ struct TileList {
     }
 };
 
+// Stage width in units of 256 bytes per row, by number of row groups: keeps
+// 3-4 KB of loads in flight per wavefront whatever the row count.
+__host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 8 : ng == 2 ? 4 : 2; }
+
 struct GramArgs {
     const void *rows[kGramRows];  // DEVICE pointers, group g = rows[16 g .. 16 g + 15]; never NULL: rows past
                                   // the last gradient alias a real one and their tile entries are dropped
@@ -68,172 +77,191 @@ struct GramArgs {
     double *ws;                   // [kGramBlocks][kGramMaxTiles][kGramTile] per-workgroup tiles
 };
 
-// ---- one step's worth of one row for one lane: 32 bytes --------------------
-template <typename T> struct GramTraits;
-template <> struct GramTraits<float> {
-    static constexpr int kLane = 8;                 // elements per lane per step
-    typedef f32x4_t raw;
-};
-template <> struct GramTraits<bf16_t> {
-    static constexpr int kLane = 16;
-    typedef u32x4_t raw;
-};
+// 16 bytes of a row starting at element p, element-wise and zero past the end.
+__device__ __forceinline__ u32x4_t gram_load_guarded(const float *row, size_t p, size_t P)
+{
+    u32x4_t v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = p + e < P ? __float_as_uint(row[p + e]) : 0u;
+    return v;
+}
+__device__ __forceinline__ u32x4_t gram_load_guarded(const bf16_t *row, size_t p, size_t P)
+{
+    u32x4_t v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const size_t q = p + 2 * e;
+        const uint32_t lo = q < P ? row[q] : 0u, hi = q + 1 < P ? row[q + 1] : 0u;
+        v[e] = lo | (hi << 16);
+    }
+    return v;
+}
 
 template <typename T>
-__device__ __forceinline__ void gram_load(const T *row, size_t p, typename GramTraits<T>::raw (&v)[2])
+__device__ __forceinline__ void gram_mma(const u32x4_t &x, const u32x4_t &y, floatx4 &acc, int e)
 {
-    typedef typename GramTraits<T>::raw raw;
-    constexpr int half = GramTraits<T>::kLane / 2;
-    v[0] = __builtin_nontemporal_load(reinterpret_cast<const raw *>(row + p));
-    v[1] = __builtin_nontemporal_load(reinterpret_cast<const raw *>(row + p + half));
-}
-__device__ __forceinline__ void gram_load_guarded(const float *row, size_t p, size_t P, f32x4_t (&v)[2])
-{
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const size_t q = p + 4 * h + e;
-            v[h][e] = q < P ? row[q] : 0.f;
-        }
-}
-__device__ __forceinline__ void gram_load_guarded(const bf16_t *row, size_t p, size_t P, u32x4_t (&v)[2])
-{
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const size_t q = p + 8 * h + 2 * e;
-            const uint32_t lo = q < P ? row[q] : 0u, hi = q + 1 < P ? row[q + 1] : 0u;
-            v[h][e] = lo | (hi << 16);
-        }
-}
-
-__device__ __forceinline__ void gram_mma(const f32x4_t (&x)[2], const f32x4_t (&y)[2], floatx4 &acc, int h, int e)
-{
-    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(x[h][e], y[h][e], acc, 0, 0, 0);
-}
-__device__ __forceinline__ void gram_mma(const u32x4_t (&x)[2], const u32x4_t (&y)[2], floatx4 &acc, int h, int)
-{
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x[h]),
-                                                  __builtin_bit_cast(bf16x8_t, y[h]), acc, 0, 0, 0);
+    if (sizeof(T) == 4)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(x[e]), __uint_as_float(y[e]), acc, 0, 0, 0);
+    else
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x),
+                                                      __builtin_bit_cast(bf16x8_t, y), acc, 0, 0, 0);
 }
 
 template <typename T, int NG, int kMode>
-__global__ __launch_bounds__(kGramThreads) void gram_kernel(GramArgs a)
+__global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
 {
     typedef TileList<NG, kMode> Tiles;
-    typedef typename GramTraits<T>::raw raw;
     constexpr int NT = Tiles::count;
-    constexpr int kLane = GramTraits<T>::kLane;
-    constexpr int kStep = 4 * kLane;                    // elements of each row per wavefront step (128 bytes)
-    constexpr int kInner = sizeof(T) == 4 ? 4 : 1;      // MFMAs per 16-byte register
+    constexpr int M = gram_stage_m(NG);
+    constexpr int kRows = 16 * NG;
+    constexpr int kRowWords = 64 * M + kGramPad;            // LDS words per row of a stage
+    constexpr int kStageWords = kRows * kRowWords;
+    constexpr int kElem16 = 16 / sizeof(T);                 // elements per 16-byte piece
+    constexpr size_t kStageElems = size_t(256) * M / sizeof(T);   // elements of each row per stage
+    constexpr int kInner = sizeof(T) == 4 ? 4 : 1;          // MFMAs per 16-byte register
+    static_assert(2 * kStageWords * 4 >= NT * kGramTile * 8, "stage buffers are reused for the final combine");
 
-    __shared__ double tot_lds[kGramWaves][NT * kGramTile];   // per-wavefront binary64 totals, <= 40 KB
+    __shared__ __attribute__((aligned(16))) uint32_t stage[2 * kStageWords];
+    __shared__ const void *row_table[kGramRows];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 15, kq = lane >> 4;
+    const int l16 = lane & 15, sub = lane >> 4;
 
-    // this lane's row in each group, selected with compile-time indices so the
-    // pointer table stays in the kernel-argument segment
-    const T *row[NG];
+    // pointer table into LDS, read with compile-time indices so that it stays in
+    // the kernel-argument segment
+    if (threadIdx.x < kRows) {
+        const void *p = nullptr;
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        row[g] = nullptr;
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-            if (r == k) row[g] = static_cast<const T *>(a.rows[16 * g + k]);
+        for (int k = 0; k < kRows; ++k)
+            if (int(threadIdx.x) == k) p = a.rows[k];
+        row_table[threadIdx.x] = p;
     }
+    __syncthreads();
+
+    // loading role: this wavefront owns rows [4 NG wave, 4 NG (wave+1)); lane = (row sub, 16-byte piece l16)
+    const T *lrow[NG];
+    int lword[NG];
+#pragma unroll
+    for (int j = 0; j < NG; ++j) {
+        const int rr = 4 * NG * wave + 4 * j + sub;
+        lrow[j] = static_cast<const T *>(row_table[rr]);
+        lword[j] = rr * kRowWords + l16 * 4;
+    }
+    // computing role: this wavefront owns columns [16 M wave, 16 M (wave+1)) words of every row;
+    // lane = (row l16 of each group, k-slot sub)
+    const int cword = l16 * kRowWords + wave * 16 * M + sub * 4;
 
     const size_t P = a.P;
-    const size_t nwaves = size_t(gridDim.x) * kGramWaves;
-    const size_t gw = size_t(blockIdx.x) * kGramWaves + wave;
+    const size_t nfull = P / kStageElems;
+    const size_t G = gridDim.x;
 
-    // Tile entry in accumulator register v of lane l: row i = 4*(l/16) + v, column j = l%16.
-    double *tot = &tot_lds[wave][(4 * kq) * 16 + r];   // + t*kGramTile + v*16
     floatx4 acc[NT];
+    double tot[NT][4];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) tot[t * kGramTile + v * 16] = 0.0;
+        for (int v = 0; v < 4; ++v) tot[t][v] = 0.0;
     }
 
-    // Hot-loop loads are unconditional (absent rows alias a real row on the host
-    // side and their tile entries are dropped later), so the compiler keeps all
-    // of a step's loads in flight behind one counter wait.
-    auto load_step = [&](size_t s, raw (&x)[NG][2]) {
-        const size_t p = s * kStep + size_t(kq) * kLane;
+    u32x4_t pre[NG][M];
+    auto gload = [&](size_t s) {
+        const size_t e0 = s * kStageElems + size_t(l16) * kElem16;
 #pragma unroll
-        for (int g = 0; g < NG; ++g) gram_load(row[g], p, x[g]);
+        for (int j = 0; j < NG; ++j)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                pre[j][m] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4_t *>(lrow[j] + e0 + size_t(m) * 16 * kElem16));
     };
-    auto compute = [&](const raw (&x)[NG][2]) {
+    auto gload_guarded = [&](size_t s) {
+        const size_t e0 = s * kStageElems + size_t(l16) * kElem16;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int j = 0; j < NG; ++j)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                pre[j][m] = gram_load_guarded(lrow[j], e0 + size_t(m) * 16 * kElem16, P);
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NG; ++j)
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                *reinterpret_cast<u32x4_t *>(&stage[buf * kStageWords + lword[j] + m * 64]) = pre[j][m];
+    };
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < M; ++c) {
+            u32x4_t x[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+                x[g] = *reinterpret_cast<const u32x4_t *>(
+                    &stage[buf * kStageWords + g * 16 * kRowWords + cword + c * 16]);
 #pragma unroll
             for (int e = 0; e < kInner; ++e)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) gram_mma(x[Tiles::ga(t)], x[Tiles::gb(t)], acc[t], h, e);
+                for (int t = 0; t < NT; ++t) gram_mma<T>(x[Tiles::ga(t)], x[Tiles::gb(t)], acc[t], e);
+        }
     };
     auto flush = [&]() {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                tot[t * kGramTile + v * 16] += (double)acc[t][v];   // this lane's own LDS slot
+                tot[t][v] += (double)acc[t][v];
                 acc[t][v] = 0.f;
             }
     };
 
-    // Full steps, two register buffers: the loads of step k+1 are in flight while
-    // step k is multiplied. The steady-state loop has no conditional loads.
-    const size_t nfull = P / kStep;
-    raw x0[NG][2], x1[NG][2];
-    int since_flush = 0;
-    auto after_step = [&]() {
-        if (++since_flush == kGramFlush) {
-            since_flush = 0;
-            flush();
-        }
-    };
-    size_t s = gw;
+    size_t s = blockIdx.x;
+    int buf = 0, since_flush = 0;
     if (s < nfull) {
-        load_step(s, x0);
-        while (s + 2 * nwaves < nfull) {
-            load_step(s + nwaves, x1);
-            compute(x0);
-            after_step();
-            load_step(s + 2 * nwaves, x0);
-            compute(x1);
-            after_step();
-            s += 2 * nwaves;
+        gload(s);
+        lstore(0);
+        __syncthreads();
+        while (s + G < nfull) {
+            gload(s + G);              // in flight during the MFMAs below
+            compute(buf);
+            if (++since_flush == kGramFlush) {
+                since_flush = 0;
+                flush();
+            }
+            lstore(buf ^ 1);           // the other buffer was last read before the previous barrier
+            __syncthreads();
+            buf ^= 1;
+            s += G;
         }
-        if (s + nwaves < nfull) {
-            load_step(s + nwaves, x1);
-            compute(x0);
-            compute(x1);
-        } else {
-            compute(x0);
-        }
+        compute(buf);
     }
-    // ragged tail (P not a multiple of the step): one wavefront, element-wise guarded loads
-    if (nfull * kStep < P && gw == nfull % nwaves) {
-        const size_t p = nfull * kStep + size_t(kq) * kLane;
-#pragma unroll
-        for (int g = 0; g < NG; ++g) gram_load_guarded(row[g], p, P, x0[g]);
-        compute(x0);
+    // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
+    if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
+        __syncthreads();
+        gload_guarded(nfull);
+        lstore(0);
+        __syncthreads();
+        compute(0);
     }
     flush();
 
-    // the workgroup's tile = its wavefronts' totals added in wavefront order
+    // Tile entry in accumulator register v of lane l: row i = 4*(l/16) + v, column j = l%16.
+    // Wavefronts add their tiles (their column quarters) into LDS one after the other.
+    double *comb = reinterpret_cast<double *>(stage);
+    for (int w = 0; w < kWaves; ++w) {
+        __syncthreads();
+        if (wave == w) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int e = t * kGramTile + (4 * sub + v) * 16 + l16;
+                    if (w == 0) comb[e] = tot[t][v];
+                    else comb[e] += tot[t][v];
+                }
+        }
+    }
     __syncthreads();
     double *out = a.ws + size_t(blockIdx.x) * kGramMaxTiles * kGramTile;
-    for (int e = threadIdx.x; e < NT * kGramTile; e += kGramThreads) {
-        double v = tot_lds[0][e];
-#pragma unroll
-        for (int w = 1; w < kGramWaves; ++w) v += tot_lds[w][e];
-        out[e] = v;
-    }
+    for (int e = threadIdx.x; e < NT * kGramTile; e += kBlock) out[e] = comb[e];
 }
 
 // Adds the per-workgroup tiles in workgroup order and scatters them into the

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/gaf.h"
+#include "gaf_batch.hpp"
 #include "gaf_gram.hpp"
 #include "gaf_pass.hpp"
 
@@ -21,6 +22,8 @@ struct gaf_ctx {
     double *partials;    // device, [3][kMaxBlocks]
     double *gram_ws;     // device, [kGramBlocks][kGramMaxTiles][kGramTile]
     double *gram_full;   // device, [max_N][max_N]
+    int32_t *accepted;   // device, [max_N] indices of accepted gradients (Gram-first schedule)
+    gaf_schedule schedule;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
     int prof_cap;
@@ -229,7 +232,7 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     g.ws = ctx->gram_ws;
     {
         Timed t(ctx, s, GAF_K_GRAM);
-        gram_kernel<T, NG, kMode><<<kGramBlocks, kGramThreads, 0, s>>>(g);
+        gram_kernel<T, NG, kMode><<<kGramBlocks, kBlock, 0, s>>>(g);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     f.ws = ctx->gram_ws;
@@ -277,6 +280,34 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
             if (rc != GAF_OK) return rc;
         }
     return GAF_OK;
+}
+
+// Gram-first schedule: Gram matrix, scalar filter, masked mean. N <= kBatchMaxN.
+template <typename T, bool kStream>
+gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
+                               float *out, uint8_t *mask, float *cos_dist, int32_t *count,
+                               hipStream_t s)
+{
+    gaf_status rc = gram_all_pairs<T>(ctx, grads, N, P, s);
+    if (rc != GAF_OK) return rc;
+    {
+        Timed t(ctx, s, GAF_K_FILTER);
+        filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, mask, cos_dist, count,
+                                       ctx->accepted);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    MeanArgs m{};
+    for (int i = 0; i < kBatchMaxN; ++i) m.rows[i] = grads[i < N ? i : 0];
+    m.N = N;
+    m.accepted_list = ctx->accepted;
+    m.st = ctx->st;
+    m.out = out;
+    m.P = P;
+    {
+        Timed t(ctx, s, GAF_K_MEAN);
+        mean_kernel<T, kStream><<<pass_blocks(P), kBlock, 0, s>>>(m);
+    }
+    return launched();
 }
 
 template <typename T>
@@ -333,13 +364,16 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->max_N = max_N;
     ctx->prof_on = false;
     ctx->prof_cap = 0;
+    ctx->schedule = GAF_SCHEDULE_AUTO;
     const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
     bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->partials),
                         sizeof(double) * 3 * kMaxBlocks) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->gram_ws), gram_ws_bytes) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void **>(&ctx->gram_full), gram_full_bytes) == hipSuccess;
+              hipMalloc(reinterpret_cast<void **>(&ctx->gram_full), gram_full_bytes) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->accepted), sizeof(int32_t) * size_t(max_N)) ==
+                  hipSuccess;
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -363,6 +397,7 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->partials) (void)hipFree(ctx->partials);
     if (ctx->gram_ws) (void)hipFree(ctx->gram_ws);
     if (ctx->gram_full) (void)hipFree(ctx->gram_full);
+    if (ctx->accepted) (void)hipFree(ctx->accepted);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;
@@ -421,6 +456,18 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
         if (misaligned(grads[i])) return GAF_EALIGN;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
+    const bool gram_first = ctx->schedule == GAF_SCHEDULE_GRAM ||
+                            (ctx->schedule == GAF_SCHEDULE_AUTO && N >= 2 && N <= kBatchMaxN);
+    if (gram_first) {
+        // the masked mean reads c gradients of s bytes and writes 4 bytes per element
+        const bool st = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
+        if (dt == GAF_F32)
+            return st ? aggregate_gram_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+                      : aggregate_gram_impl<float, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+        return st ? aggregate_gram_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+                  : aggregate_gram_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+    }
     if (dt == GAF_F32)
         return stream_loads(P, 4)
                    ? aggregate_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
@@ -428,6 +475,16 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
     return stream_loads(P, 2)
                ? aggregate_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
                : aggregate_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+}
+
+gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule)
+{
+    if (!ctx) return GAF_EINVAL;
+    if (schedule != GAF_SCHEDULE_AUTO && schedule != GAF_SCHEDULE_SEQUENTIAL &&
+        schedule != GAF_SCHEDULE_GRAM)
+        return GAF_EINVAL;
+    ctx->schedule = schedule;
+    return GAF_OK;
 }
 
 gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,

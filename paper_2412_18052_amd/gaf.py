@@ -16,8 +16,11 @@ GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEV
 GAF_F32, GAF_BF16 = 0, 1
 
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
-           "gaf_profile_begin", "gaf_profile_end")
-KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide")
+           "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule")
+GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
+SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
+KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
+                "filter", "mean")
 
 
 class LaunchTime(ctypes.Structure):
@@ -60,6 +63,8 @@ def load(path=None):
     lib.gaf_pairwise.restype = c.c_int
     lib.gaf_pairwise.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
                                  c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_set_schedule.restype = c.c_int
+    lib.gaf_set_schedule.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_begin.restype = c.c_int
     lib.gaf_profile_begin.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_end.restype = c.c_int
@@ -142,6 +147,12 @@ def gaf_destroy(ctx):
 
 def gaf_strerror(status):
     return strerror(status)
+
+
+def gaf_set_schedule(ctx, schedule):
+    """schedule: "auto" | "sequential" | "gram" (or the integer code)."""
+    code = SCHEDULES[schedule] if isinstance(schedule, str) else int(schedule)
+    _check(load().gaf_set_schedule(ctx.handle, code), "gaf_set_schedule")
 
 
 def gaf_aggregate(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,

@@ -23,10 +23,14 @@ OUT_RTOL = {"f32": 1e-5, "bf16": 2e-3}
 TILE = 256 * 4 * 4          # elements one workgroup handles per tile
 
 
-@pytest.fixture(scope="module")
-def ctx():
+# Every test runs under both schedules of gaf_aggregate: "sequential" (one fused
+# streaming pass per gradient) and "auto" (Gram-first for N <= 64, the default).
+@pytest.fixture(scope="module", params=["sequential", "auto"])
+def ctx(request):
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     c = gaf.gaf_create(max_P=1 << 31, max_N=256)
+    gaf.gaf_set_schedule(c, request.param)
+    c.schedule_name = request.param
     yield c
     torch.cuda.synchronize()
     gaf.gaf_destroy(c)
@@ -284,7 +288,7 @@ def test_argument_errors(ctx):
     lib = gaf.load()
     P = 4096
     x = torch.randn(P + 8, device="cuda"); out = torch.empty(P + 8, device="cuda")
-    mask = torch.empty(4, dtype=torch.uint8, device="cuda"); dist = torch.empty(4, device="cuda")
+    mask = torch.empty(80, dtype=torch.uint8, device="cuda"); dist = torch.empty(80, device="cuda")
     count = torch.zeros(1, dtype=torch.int32, device="cuda")
 
     def agg(ptrs, N, P_, dt, outp):
@@ -301,6 +305,13 @@ def test_argument_errors(ctx):
     assert agg([xp, xp], 2, P, 7, op) == gaf.GAF_EUNSUPPORTED     # unknown dtype
     assert agg([xp, op], 2, P, 0, op) == gaf.GAF_EINVAL           # out aliases an input
     assert agg([xp] * 257, 257, P, 0, op) == gaf.GAF_EINVAL       # beyond the context's max_N
+    assert lib.gaf_set_schedule(ctx.handle, 9) == gaf.GAF_EINVAL
+    assert lib.gaf_set_schedule(ctx.handle, gaf.GAF_SCHEDULE_GRAM) == gaf.GAF_OK
+    assert agg([xp] * 65, 65, P, 0, op) == gaf.GAF_EUNSUPPORTED   # Gram-first handles at most 64
+    assert agg([xp], 1, P, 0, op) == gaf.GAF_EUNSUPPORTED
+    assert lib.gaf_set_schedule(ctx.handle, gaf.GAF_SCHEDULE_AUTO) == gaf.GAF_OK
+    assert agg([xp] * 65, 65, P, 0, op) == gaf.GAF_OK             # auto falls back to sequential
+    gaf.gaf_set_schedule(ctx, ctx.schedule_name)
     assert lib.gaf_step(ctx.handle, op, count.data_ptr(), xp + 2, P, 1, 1.0, None, None, None) == gaf.GAF_EALIGN
     assert lib.gaf_step(ctx.handle, op, None, xp, P, 0, 1.0, None, None, None) == gaf.GAF_EINVAL
     assert lib.gaf_pairwise(ctx.handle, (ctypes.c_void_p * 1)(xp), 1, P, 0, None, None, None) == gaf.GAF_EINVAL
