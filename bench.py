@@ -26,6 +26,8 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
+PEAK_VALU_F64_TFLOPS = 78.6   # MI355X fp64 vector, published
 
 
 def source_digest():
@@ -54,6 +56,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large",
                     choices=["tiny", "resnet18", "streaming", "large", "diagnostic"])
+    ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "gram"],
+                    help="schedule of the batch call (auto = Gram-first for N <= 64)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--P", type=int, default=None, help="override the vector length")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
@@ -91,6 +95,13 @@ def main():
     gen_s = time.time() - t0
     P, N, s = w.P, w.N, w.elem_bytes
     ctx = gaf.gaf_create(max_P=P, max_N=max(N, 64))
+    gaf.gaf_set_schedule(ctx, args.schedule)
+    if w.mode == "step":
+        schedule_used = "streaming"
+    elif args.schedule == "sequential" or not (2 <= N <= 64):
+        schedule_used = "sequential"
+    else:
+        schedule_used = "gram_first"
 
     out = torch.empty(P, dtype=torch.float32, device="cuda")
     mask = torch.empty(N, dtype=torch.uint8, device="cuda")
@@ -137,24 +148,47 @@ def main():
     for name, ms in times:
         per_kernel.setdefault(name, []).append(ms)
     launches_per_step = len(times) // args.steps
-    if w.mode == "pairwise":
-        dom = "gram"
+
+    # algorithmic bytes (and MFMA flops) per launch of each streaming kernel
+    def hbm_roof(alg_bytes, avg_ms):
+        ach = alg_bytes / (avg_ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBPS}
+
+    roofs = {}
+    if "gram" in per_kernel:
+        # one launch reads every gradient once
         dur = per_kernel["gram"]
-        alg_bytes = float(N * s * P)
-        flops = 2.0 * 3 * 32 * 32 * P          # three 32x32 tiles, one multiply-add per entry per element
         avg_ms = sum(dur) / len(dur)
-        hbm_frac = alg_bytes / (avg_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS
-        mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS
-        if mfma_frac >= hbm_frac:
-            roof = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12,
-                    "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac}
+        alg_bytes = float(N * s * P)
+        r = hbm_roof(alg_bytes, avg_ms)
+        if N <= 8:
+            # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
+            flops = 2.0 * (N * (N + 1) // 2) * P
+            frac2 = flops / (avg_ms * 1e-3) / 1e12 / PEAK_VALU_F64_TFLOPS
+            if frac2 > r["frac"]:
+                r = {"bound": "alu", "achieved": flops / (avg_ms * 1e-3) / 1e12,
+                     "peak": PEAK_VALU_F64_TFLOPS, "unit": "TFLOP/s", "frac": frac2, "hbm_frac": r["frac"]}
+            else:
+                r["alu_frac"] = frac2
         else:
-            roof = {"bound": "hbm", "achieved": alg_bytes / (avg_ms * 1e-3) / 1e9,
-                    "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": hbm_frac}
-        roof["hbm_frac"] = hbm_frac
-        roof["mfma_frac"] = mfma_frac
-    else:
-        dom = "reduce"
+            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups
+            ng = (N + 15) // 16
+            flops = 2.0 * (ng * (ng + 1) // 2) * 256 * P
+            peak_tf = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
+            mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / peak_tf
+            if mfma_frac > r["frac"]:
+                r = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": peak_tf,
+                     "unit": "TFLOP/s", "frac": mfma_frac, "hbm_frac": r["frac"]}
+            else:
+                r["mfma_frac"] = mfma_frac
+        roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
+    if "mean" in per_kernel:
+        dur = per_kernel["mean"]
+        avg_ms = sum(dur) / len(dur)
+        alg_bytes = float(c_h * s * P + 4 * P)      # accepted gradients read once, result written once
+        roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
+    if "reduce" in per_kernel:
         # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
         # gradient i - 1 if that one was accepted; a streaming reduce never stores.
         if w.mode == "step":
@@ -162,27 +196,46 @@ def main():
             per_launch = [None] + [(4 + s) * P] * (N - 1)
         else:
             per_launch = [(4 + s) * P + (4 * P if mask_h[i - 1] else 0) for i in range(2, N)]
-        dur = per_kernel.get("reduce", [])
+        dur = per_kernel["reduce"]
         n_per_step = len(per_launch)
         assert len(dur) == n_per_step * args.steps, (len(dur), n_per_step, args.steps)
         dur = [d for k, d in enumerate(dur) if per_launch[k % n_per_step] is not None]
         alg = sum(b for b in per_launch if b is not None) * args.steps
         avg_ms = sum(dur) / max(1, len(dur))
         alg_bytes = alg / max(1, len(dur))
-        ach = alg_bytes / (avg_ms * 1e-3) / 1e9 if dur else 0.0
-        roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBPS}
+        roofs["reduce"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
+    dom = max(roofs, key=lambda k: roofs[k][3])      # the kernel the step spends most time in
+    roof, avg_ms, alg_bytes, _ = roofs[dom]
     roof["kernel"] = dom
     roof["avg_launch_ms"] = avg_ms
     roof["algorithmic_bytes_per_launch"] = alg_bytes
     roof["traffic"] = None
+    roof["other_kernels"] = {k: {"frac": v[0]["frac"], "bound": v[0]["bound"], "avg_launch_ms": v[1],
+                                 "algorithmic_bytes_per_launch": v[2]}
+                             for k, v in roofs.items() if k != dom}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as fh:
             tj = json.load(fh)
-        ent = tj.get("%s/%s" % (w.name, dom))
+        ent = tj.get("%s/%s/%s" % (w.name, schedule_used, dom))
         if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
             roof["traffic"] = ent["hbm_bytes_per_launch"]
+
+    # ---- the other schedule of the batch call, for comparison (fewer steps) ----
+    other = None
+    if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64:
+        gaf.gaf_set_schedule(ctx, "sequential")
+        k = max(3, args.steps // 4)
+        step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            step()
+        torch.cuda.synchronize()
+        ms_seq = 1e3 * (time.perf_counter() - t0) / k
+        other = {"schedule": "sequential", "steps": k, "ms_per_step": ms_seq,
+                 "value": step_bytes / (ms_seq * 1e-3) / 1e9}
+        gaf.gaf_set_schedule(ctx, args.schedule)
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     cpu = None
@@ -240,11 +293,12 @@ def main():
                         % w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau,
-                   "mode": w.mode, "seed": args.seed, "accepted": c_h,
+                   "mode": w.mode, "schedule": schedule_used, "seed": args.seed, "accepted": c_h,
                    "algorithmic_bytes_per_step": step_bytes,
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "other_schedule": other,
         "kernel_ms": {k: sum(v) / len(v) for k, v in per_kernel.items()},
         "accept_mask": mask_h,
         "cos_dist": [round(x, 6) for x in dist_h],

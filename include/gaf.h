@@ -180,6 +180,20 @@ gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
                         float *D, double *gram, void *stream);
 
 /*
+ * Batch aggregation for a caller that already holds the inner products of the
+ * same gradients: `gram` (DEVICE, N*N binary64, row-major) as written by
+ * gaf_pairwise on this stream or synchronised before. Algorithm 1 is replayed
+ * on the matrix and Eq. 5 is formed as in the Gram-first schedule; the Gram
+ * pass itself is skipped, so the distance matrix of Fig. 1c/d and the filtered
+ * macro-gradient together cost one read of every gradient plus one read of the
+ * accepted ones. 1 <= N <= 64 (GAF_EUNSUPPORTED beyond); other arguments as in
+ * gaf_aggregate.
+ */
+gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                   gaf_dtype dt, float tau, const double *gram, float *out,
+                                   uint8_t *accept_mask, float *cos_dist, int32_t *count, void *stream);
+
+/*
  * Launch timing, for benchmarks (not part of the paper's method). Between
  * gaf_profile_begin and gaf_profile_end every kernel the context enqueues is
  * bracketed by a pair of HIP events on the call's stream (up to max_launches

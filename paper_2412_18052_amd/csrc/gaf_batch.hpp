@@ -22,11 +22,12 @@ constexpr int kBatchMaxN = 64;   // gradients the Gram-first schedule handles (o
 // One wavefront. Visits g_2..g_N in order exactly as Algorithm 1 does, with the
 // three sums of Eq. 4 taken from the Gram matrix. Lane k carries the k-th
 // accepted index; the dot product is a fixed-tree wavefront sum.
-__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
-                                                    uint8_t *mask, float *cos_dist, int32_t *count,
-                                                    int32_t *accepted_list)
+// Runs on ONE full wavefront (all 64 lanes active).
+__device__ __forceinline__ void run_filter(const double *gram, int N, float tau, State *st,
+                                           uint8_t *mask, float *cos_dist, int32_t *count,
+                                           int32_t *accepted_list)
 {
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
     int my_index = lane == 0 ? 0 : -1;      // lane k < c holds the k-th accepted gradient
     int c = 1;
     double nn_g = gram[0];                  // |running sum|^2
@@ -57,6 +58,133 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
         st->count = c;
         st->accept = 0;
         st->seed = 0;
+    }
+}
+
+__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
+                                                    uint8_t *mask, float *cos_dist, int32_t *count,
+                                                    int32_t *accepted_list)
+{
+    run_filter(gram, N, tau, st, mask, cos_dist, count, accepted_list);
+}
+
+// ---- small batches (N <= 8): inner products on the vector ALU in binary64 ----
+// With few rows the matrix-core tiles would be mostly padding (a 16-row group
+// is the smallest unit), while N (N + 1) / 2 <= 36 binary64 accumulators fit in
+// registers. Products of widened binary32/bfloat16 values are exact in binary64,
+// every load is a fully coalesced 16-byte (8-byte for bf16) load, and at 8 TB/s
+// the FMAs need under a third of the binary64 issue rate.
+constexpr int kSmallMaxN = 8;
+constexpr int kSmallMaxPairs = kSmallMaxN * (kSmallMaxN + 1) / 2;
+constexpr int kSmallBlocks = 512;       // workgroups of the small-batch Gram kernel (<= kMaxBlocks)
+
+struct SmallGramArgs {
+    const void *rows[kSmallMaxN];
+    size_t P;
+    double *partials;     // [pairs][kMaxBlocks]
+};
+
+template <typename T, int N, bool kStream>
+__global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
+{
+    constexpr int NP = N * (N + 1) / 2;
+    constexpr int U = N <= 4 ? 4 : 2;                       // 16-byte units per thread per tile
+    constexpr size_t tile = size_t(kBlock) * U * 4;
+    __shared__ double lds[NP][kWaves];
+
+    const T *row[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) row[i] = static_cast<const T *>(a.rows[i]);
+    double acc[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) acc[k] = 0.0;
+
+    auto add = [&](const float (&x)[N]) {
+        double d[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) d[i] = (double)x[i];
+        int k = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+#pragma unroll
+            for (int j = i; j < N; ++j, ++k) acc[k] = __builtin_fma(d[i], d[j], acc[k]);
+    };
+
+    const size_t P = a.P;
+    const size_t ntiles = (P + tile - 1) / tile;
+    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const size_t base = t * tile + size_t(threadIdx.x) * 4;
+        if ((t + 1) * tile <= P) {
+            float4 v[U][N];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i) v[u][i] = load4<kStream>(row[i], base + size_t(u) * kBlock * 4);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float x[N];
+#pragma unroll
+                for (int i = 0; i < N; ++i) x[i] = v[u][i].x;
+                add(x);
+#pragma unroll
+                for (int i = 0; i < N; ++i) x[i] = v[u][i].y;
+                add(x);
+#pragma unroll
+                for (int i = 0; i < N; ++i) x[i] = v[u][i].z;
+                add(x);
+#pragma unroll
+                for (int i = 0; i < N; ++i) x[i] = v[u][i].w;
+                add(x);
+            }
+        } else {
+            for (int u = 0; u < U; ++u)
+                for (int e = 0; e < 4; ++e) {
+                    const size_t idx = base + size_t(u) * kBlock * 4 + e;
+                    if (idx >= P) continue;
+                    float x[N];
+#pragma unroll
+                    for (int i = 0; i < N; ++i) x[i] = load1(row[i], idx);
+                    add(x);
+                }
+        }
+    }
+    // workgroup sums: DPP tree per wavefront, wavefronts added in order
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const double v = wave_sum(acc[k]);
+        if (lane == 0) lds[k][wave] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < NP) {
+        double v = lds[threadIdx.x][0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) v += lds[threadIdx.x][w];
+        a.partials[size_t(threadIdx.x) * kMaxBlocks + blockIdx.x] = v;
+    }
+}
+
+// One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner
+// products (strided per thread, then the fixed wavefront and workgroup trees)
+// and writes both mirror entries of the Gram matrix (leading dimension N).
+// (A single workgroup doing all pairs in turn was measured at 50-70 us for 36
+// pairs x 1370 partials: one memory round trip per pair, serialised.)
+__global__ __launch_bounds__(kBlock) void gram_small_finalize_kernel(const double *partials, int nb, int N,
+                                                                     double *gram)
+{
+    const int k = blockIdx.x;
+    double s = 0.0, z0 = 0.0, z1 = 0.0;
+    for (int b = threadIdx.x; b < nb; b += kBlock) s += partials[size_t(k) * kMaxBlocks + b];
+    block_sum3(s, z0, z1);
+    if (threadIdx.x == 0) {
+        int i = 0, left = k;              // pair index k -> (i, j), j >= i, row-major upper triangle
+        while (left >= N - i) {
+            left -= N - i;
+            ++i;
+        }
+        const int j = i + left;
+        gram[i * N + j] = s;
+        gram[j * N + i] = s;
     }
 }
 
@@ -97,11 +225,7 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
             float4 sum[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) sum[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int k = 0; k < c; ++k) {
-                const T *g = static_cast<const T *>(table[list[k]]);
-                float4 v[kUnroll];
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) v[u] = load4<kStream>(g, base + size_t(u) * kBlock * 4);
+            auto add4 = [&](const float4 (&v)[kUnroll]) {
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     sum[u].x += v[u].x;
@@ -109,6 +233,25 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
                     sum[u].z += v[u].z;
                     sum[u].w += v[u].w;
                 }
+            };
+            int k = 0;
+            for (; k + 1 < c; k += 2) {      // two gradients' loads in flight together
+                const T *g0 = static_cast<const T *>(table[list[k]]);
+                const T *g1 = static_cast<const T *>(table[list[k + 1]]);
+                float4 v0[kUnroll], v1[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) v0[u] = load4<kStream>(g0, base + size_t(u) * kBlock * 4);
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) v1[u] = load4<kStream>(g1, base + size_t(u) * kBlock * 4);
+                add4(v0);
+                add4(v1);
+            }
+            if (k < c) {
+                const T *g0 = static_cast<const T *>(table[list[k]]);
+                float4 v0[kUnroll];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) v0[u] = load4<kStream>(g0, base + size_t(u) * kBlock * 4);
+                add4(v0);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)

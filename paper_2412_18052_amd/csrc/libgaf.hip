@@ -283,17 +283,61 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
 }
 
 // Gram-first schedule: Gram matrix, scalar filter, masked mean. N <= kBatchMaxN.
-template <typename T, bool kStream>
-gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
-                               float *out, uint8_t *mask, float *cos_dist, int32_t *count,
-                               hipStream_t s)
+// N <= kSmallMaxN: binary64 vector-ALU inner products into ctx->gram_full.
+template <typename T, bool kStream, int N>
+gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 {
-    gaf_status rc = gram_all_pairs<T>(ctx, grads, N, P, s);
+    gram_small_kernel<T, N, kStream><<<nb, kBlock, 0, s>>>(g);
+    return launched();
+}
+
+template <typename T, bool kStream>
+gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s)
+{
+    SmallGramArgs g{};
+    for (int i = 0; i < kSmallMaxN; ++i) g.rows[i] = grads[i < N ? i : 0];
+    g.P = P;
+    g.partials = ctx->gram_ws;
+    // at most two workgroups per CU: few partial sums to combine afterwards, and the widest
+    // variant (N = 8) does not fit more anyway
+    const int nb = pass_blocks(P) < kSmallBlocks ? pass_blocks(P) : kSmallBlocks;
+    gaf_status rc = GAF_OK;
+    {
+        Timed t(ctx, s, GAF_K_GRAM);
+        switch (N) {
+        case 1: rc = gram_small_launch<T, kStream, 1>(g, nb, s); break;
+        case 2: rc = gram_small_launch<T, kStream, 2>(g, nb, s); break;
+        case 3: rc = gram_small_launch<T, kStream, 3>(g, nb, s); break;
+        case 4: rc = gram_small_launch<T, kStream, 4>(g, nb, s); break;
+        case 5: rc = gram_small_launch<T, kStream, 5>(g, nb, s); break;
+        case 6: rc = gram_small_launch<T, kStream, 6>(g, nb, s); break;
+        case 7: rc = gram_small_launch<T, kStream, 7>(g, nb, s); break;
+        default: rc = gram_small_launch<T, kStream, 8>(g, nb, s); break;
+        }
+    }
     if (rc != GAF_OK) return rc;
     {
+        Timed t(ctx, s, GAF_K_GRAM_FINALIZE);
+        gram_small_finalize_kernel<<<N * (N + 1) / 2, kBlock, 0, s>>>(ctx->gram_ws, nb, N, ctx->gram_full);
+    }
+    return launched();
+}
+
+// `gram` non-null: the caller's matrix of inner products is used and the Gram pass is skipped.
+template <typename T, bool kStream>
+gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
+                               const double *gram, float *out, uint8_t *mask, float *cos_dist,
+                               int32_t *count, hipStream_t s)
+{
+    if (!gram) {
+        const gaf_status rc = N <= kSmallMaxN ? gram_small<T, kStream>(ctx, grads, N, P, s)
+                                              : gram_all_pairs<T>(ctx, grads, N, P, s);
+        if (rc != GAF_OK) return rc;
+        gram = ctx->gram_full;
+    }
+    {
         Timed t(ctx, s, GAF_K_FILTER);
-        filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, mask, cos_dist, count,
-                                       ctx->accepted);
+        filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     MeanArgs m{};
@@ -314,7 +358,13 @@ template <typename T>
 gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float *D,
                          double *gram_out, hipStream_t s)
 {
-    const gaf_status rc = gram_all_pairs<T>(ctx, grads, N, P, s);
+    gaf_status rc;
+    if (N <= kSmallMaxN)
+        rc = (size_t(N) * sizeof(T) * P > (size_t(256) << 20))
+                 ? gram_small<T, true>(ctx, grads, N, P, s)
+                 : gram_small<T, false>(ctx, grads, N, P, s);
+    else
+        rc = gram_all_pairs<T>(ctx, grads, N, P, s);
     if (rc != GAF_OK) return rc;
     const int n2 = N * N;
     {
@@ -323,6 +373,19 @@ gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P
                                                                              gram_out);
     }
     return launched();
+}
+
+gaf_status gram_first_dispatch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                               float tau, const double *gram, float *out, uint8_t *mask,
+                               float *cos_dist, int32_t *count, hipStream_t s)
+{
+    // the masked mean reads up to N gradients of s bytes and writes 4 bytes per element
+    const bool st = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
+    if (dt == GAF_F32)
+        return st ? aggregate_gram_impl<float, true>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s)
+                  : aggregate_gram_impl<float, false>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s);
+    return st ? aggregate_gram_impl<bf16_t, true>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s)
+              : aggregate_gram_impl<bf16_t, false>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s);
 }
 
 }  // namespace
@@ -459,15 +522,8 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
     if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
     const bool gram_first = ctx->schedule == GAF_SCHEDULE_GRAM ||
                             (ctx->schedule == GAF_SCHEDULE_AUTO && N >= 2 && N <= kBatchMaxN);
-    if (gram_first) {
-        // the masked mean reads c gradients of s bytes and writes 4 bytes per element
-        const bool st = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
-        if (dt == GAF_F32)
-            return st ? aggregate_gram_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
-                      : aggregate_gram_impl<float, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
-        return st ? aggregate_gram_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
-                  : aggregate_gram_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
-    }
+    if (gram_first)
+        return gram_first_dispatch(ctx, grads, N, P, dt, tau, nullptr, out, accept_mask, cos_dist, count, s);
     if (dt == GAF_F32)
         return stream_loads(P, 4)
                    ? aggregate_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
@@ -475,6 +531,26 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
     return stream_loads(P, 2)
                ? aggregate_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
                : aggregate_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+}
+
+gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                   gaf_dtype dt, float tau, const double *gram, float *out,
+                                   uint8_t *accept_mask, float *cos_dist, int32_t *count, void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!grads || N < 1 || P == 0 || !gram || !out || !accept_mask || !cos_dist || !count)
+        return GAF_EINVAL;
+    if (N > ctx->max_N || P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (N > kBatchMaxN) return GAF_EUNSUPPORTED;
+    if (misaligned(out)) return GAF_EALIGN;
+    for (int i = 0; i < N; ++i) {
+        if (!grads[i] || grads[i] == static_cast<const void *>(out)) return GAF_EINVAL;
+        if (misaligned(grads[i])) return GAF_EALIGN;
+    }
+    return gram_first_dispatch(ctx, grads, N, P, dt, tau, gram, out, accept_mask, cos_dist, count,
+                               static_cast<hipStream_t>(stream));
 }
 
 gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule)

@@ -16,7 +16,7 @@ GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEV
 GAF_F32, GAF_BF16 = 0, 1
 
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
-           "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule")
+           "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -63,6 +63,10 @@ def load(path=None):
     lib.gaf_pairwise.restype = c.c_int
     lib.gaf_pairwise.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
                                  c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_aggregate_with_gram.restype = c.c_int
+    lib.gaf_aggregate_with_gram.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
+                                            c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
+                                            c.c_void_p, c.c_void_p, c.c_void_p]
     lib.gaf_set_schedule.restype = c.c_int
     lib.gaf_set_schedule.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_begin.restype = c.c_int
@@ -169,6 +173,24 @@ def gaf_aggregate(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, co
     _check(load().gaf_aggregate(ctx.handle, table, N, P, code, float(tau), _ptr(out),
                                 _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
                                 _stream_handle(stream)), "gaf_aggregate")
+    return out, accept_mask, cos_dist, count
+
+
+def gaf_aggregate_with_gram(ctx, grads, tau, gram, out=None, accept_mask=None, cos_dist=None,
+                            count=None, stream=None):
+    """Batch aggregation reusing the Gram matrix gaf_pairwise wrote (N x N float64 device tensor)."""
+    table, P, code = _grad_table(grads)
+    dev = grads[0].device
+    N = len(grads)
+    if gram.dtype != torch.float64 or gram.numel() != N * N or not gram.is_contiguous():
+        raise ValueError("gram must be a contiguous N x N float64 device tensor")
+    out = torch.empty(P, dtype=torch.float32, device=dev) if out is None else out
+    accept_mask = torch.empty(N, dtype=torch.uint8, device=dev) if accept_mask is None else accept_mask
+    cos_dist = torch.empty(N, dtype=torch.float32, device=dev) if cos_dist is None else cos_dist
+    count = torch.empty(1, dtype=torch.int32, device=dev) if count is None else count
+    _check(load().gaf_aggregate_with_gram(ctx.handle, table, N, P, code, float(tau), _ptr(gram),
+                                          _ptr(out), _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
+                                          _stream_handle(stream)), "gaf_aggregate_with_gram")
     return out, accept_mask, cos_dist, count
 
 

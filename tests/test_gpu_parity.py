@@ -116,6 +116,9 @@ def test_diagnostic_scaled(ctx, oracle):
     # first row of the matrix = sequential distances until the first acceptance
     first = int(np.argmax(ref[1][1:])) + 1
     assert np.max(np.abs(Dh[0, 1:first + 1] - ref[2][1:first + 1])) <= DIST_ATOL
+    # the filter replayed on the matrix gaf_pairwise has just written
+    res2 = gaf.gaf_aggregate_with_gram(ctx, dev, w.tau, gram)
+    check_against_oracle(res2, ref, w.dtype)
 
 
 # ------------------------------------------------------------ shapes / tails --
@@ -154,6 +157,25 @@ def test_small_N(ctx, oracle, N):
     grads = [torch.randn(70_001, generator=g) for _ in range(N)]
     for tau in (2.0, -0.5):
         run_aggregate(ctx, oracle, grads, tau)
+
+
+@pytest.mark.parametrize("N", [2, 4, 5, 7, 8, 9, 16, 17, 31, 48, 49, 64])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_batch_sizes(ctx, oracle, N, dtype):
+    # every kernel variant of the batch call: vector-ALU Gram (N <= 8), 1..4 row groups of the
+    # matrix-core Gram, ragged P
+    P = 150_001 + 1000 * N
+    name = "large" if dtype == "bf16" else "resnet18"
+    w, grads, ref = workload_with_margin(name, P=P, N=N, seed=N)
+    dev = [g.cuda() for g in grads]
+    res = gaf.gaf_aggregate(ctx, dev, w.tau)
+    check_against_oracle(res, ref, dtype)
+    gram = torch.empty((N, N), dtype=torch.float64, device="cuda")
+    D = gaf.gaf_pairwise(ctx, dev, gram=gram)
+    res2 = gaf.gaf_aggregate_with_gram(ctx, dev, w.tau, gram)
+    check_against_oracle(res2, ref, dtype)
+    oD, oG = oracle.pairwise(oracle_arrays(grads))
+    assert np.max(np.abs(D.cpu().numpy().astype(np.float64) - oD)) <= DIST_ATOL
 
 
 # ------------------------------------------------------- limiting cases -------
