@@ -108,6 +108,9 @@ def main():
     dist = torch.empty(N, dtype=torch.float32, device="cuda")
     count = torch.zeros(1, dtype=torch.int32, device="cuda")
     D = torch.empty((N, N), dtype=torch.float32, device="cuda") if w.mode == "pairwise" else None
+    G = torch.empty((N, N), dtype=torch.float64, device="cuda") if w.mode == "pairwise" else None
+
+    state = {"schedule": args.schedule}
 
     def step():
         if w.mode == "step":
@@ -115,6 +118,11 @@ def main():
             for i, g in enumerate(grads):
                 gaf.gaf_step(ctx, out, count, g, w.tau, dist[i:i + 1], mask[i:i + 1])
         else:
+            if w.mode == "pairwise" and state["schedule"] != "sequential":
+                # the distance matrix and the filter share one Gram pass
+                gaf.gaf_pairwise(ctx, grads, D=D, gram=G)
+                gaf.gaf_aggregate_with_gram(ctx, grads, w.tau, G, out, mask, dist, count)
+                return
             if w.mode == "pairwise":
                 gaf.gaf_pairwise(ctx, grads, D=D)
             gaf.gaf_aggregate(ctx, grads, w.tau, out, mask, dist, count)
@@ -225,6 +233,7 @@ def main():
     other = None
     if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64:
         gaf.gaf_set_schedule(ctx, "sequential")
+        state["schedule"] = "sequential"
         k = max(3, args.steps // 4)
         step()
         torch.cuda.synchronize()
@@ -236,6 +245,7 @@ def main():
         other = {"schedule": "sequential", "steps": k, "ms_per_step": ms_seq,
                  "value": step_bytes / (ms_seq * 1e-3) / 1e9}
         gaf.gaf_set_schedule(ctx, args.schedule)
+        state["schedule"] = args.schedule
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     cpu = None
