@@ -205,3 +205,110 @@ int oracle_gaf_pairwise(const void *const *grads, int N, size_t P, int dtype, do
     free(gram);
     return 0;
 }
+
+/*
+ * Order-indifferent variant (Sec. 3.1, last paragraph; "Order Indifference"
+ * under future research): every micro-gradient acts as the seed in turn, the
+ * others are visited in ring order behind it (s, s+1, .., N-1, 0, .., s-1),
+ * and the run with the largest agreement is the one that is kept.
+ * Readings: "agreement" = number of accepted gradients c; ties go to the
+ * lowest seed index. Outputs are indexed by ORIGINAL gradient index: mask[i],
+ * and dist[i] = the distance of g_i when it was visited in the winning run
+ * (0 for the seed). counts_all (nullable, N entries) receives c of every run.
+ */
+int oracle_gaf_best_seed(const void *const *grads, int N, size_t P, int dtype, double tau,
+                         double *out, uint8_t *mask, double *dist, int32_t *count, int32_t *seed,
+                         int32_t *counts_all)
+{
+    if (!grads || N < 1 || !out || !mask || !dist || !count || !seed)
+        return 1;
+    const void **ring = (const void **)malloc(sizeof(void *) * (size_t)N);
+    double *tmp = (double *)malloc(sizeof(double) * P);
+    uint8_t *m = (uint8_t *)malloc((size_t)N);
+    double *d = (double *)malloc(sizeof(double) * (size_t)N);
+    if (!ring || !tmp || !m || !d)
+        return 2;
+    int best = -1;
+    int32_t best_c = 0;
+    for (int s = 0; s < N; ++s) {
+        for (int k = 0; k < N; ++k)
+            ring[k] = grads[(s + k) % N];
+        int32_t c = 0;
+        int rc = oracle_gaf_aggregate(ring, N, P, dtype, tau, tmp, m, d, &c);
+        if (rc)
+            return rc;
+        if (counts_all)
+            counts_all[s] = c;
+        if (c > best_c) {
+            best = s;
+            best_c = c;
+            memcpy(out, tmp, sizeof(double) * P);
+            for (int k = 0; k < N; ++k) {
+                mask[(s + k) % N] = m[k];
+                dist[(s + k) % N] = d[k];
+            }
+        }
+    }
+    *count = best_c;
+    *seed = best;
+    free(ring);
+    free(tmp);
+    free(m);
+    free(d);
+    return 0;
+}
+
+/*
+ * GAF-SGD step: Eq. 6 with the optimizer the experiments name (Sec. 4.1: SGD
+ * with momentum, L2 regularisation through a weight decay), and Algorithm 1's
+ * skip: if c == 1 neither the parameters nor the optimizer state are touched.
+ * Readings: the momentum form is the common heavy-ball one with the decay
+ * folded into the gradient,
+ *     d = g_GAF + wd * theta;   v <- mu * v + d;   theta <- theta - lr * v,
+ * no dampening, no Nesterov look-ahead; v starts at zero.
+ * g_gaf is the output of the aggregation, c its count.
+ */
+int oracle_sgd_step(double *theta, double *v, const double *g_gaf, int32_t c, size_t P, double lr,
+                    double mu, double wd)
+{
+    if (!theta || !v || !g_gaf)
+        return 1;
+    if (c <= 1)
+        return 0;
+#pragma omp parallel for schedule(static)
+    for (size_t p = 0; p < P; ++p) {
+        double d = g_gaf[p] + wd * theta[p];
+        v[p] = mu * v[p] + d;
+        theta[p] = theta[p] - lr * v[p];
+    }
+    return 0;
+}
+
+/*
+ * Bucketed GAF ("cosine distance to buckets at a time", future research): the
+ * parameter vector is cut into B contiguous buckets [off[b], off[b+1]) and
+ * Algorithm 1 runs independently inside each bucket. mask and dist are B x N
+ * row-major, count has B entries, out has P entries.
+ */
+int oracle_gaf_bucketed(const void *const *grads, int N, size_t P, int dtype, double tau, int B,
+                        const size_t *off, double *out, uint8_t *mask, double *dist, int32_t *count)
+{
+    if (!grads || N < 1 || B < 1 || !off || off[0] != 0 || off[B] != P)
+        return 1;
+    const size_t es = dtype == ORACLE_F32 ? 4 : 2;
+    const void **sl = (const void **)malloc(sizeof(void *) * (size_t)N);
+    if (!sl)
+        return 2;
+    for (int b = 0; b < B; ++b) {
+        if (off[b + 1] <= off[b])
+            return 1;
+        for (int i = 0; i < N; ++i)
+            sl[i] = (const char *)grads[i] + off[b] * es;
+        int rc = oracle_gaf_aggregate(sl, N, off[b + 1] - off[b], dtype, tau, out + off[b],
+                                      mask + (size_t)b * N, dist + (size_t)b * N, &count[b]);
+        if (rc)
+            return rc;
+    }
+    free(sl);
+    return 0;
+}

@@ -61,6 +61,14 @@ def _load():
     lib.oracle_gaf_pairwise.restype = c.c_int
     lib.oracle_gaf_pairwise.argtypes = [c.c_void_p, c.c_int, c.c_size_t, c.c_int, c.c_void_p,
                                         c.c_void_p]
+    lib.oracle_gaf_best_seed.restype = c.c_int
+    lib.oracle_gaf_best_seed.argtypes = [c.c_void_p, c.c_int, c.c_size_t, c.c_int, c.c_double] + [c.c_void_p] * 6
+    lib.oracle_sgd_step.restype = c.c_int
+    lib.oracle_sgd_step.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_size_t,
+                                    c.c_double, c.c_double, c.c_double]
+    lib.oracle_gaf_bucketed.restype = c.c_int
+    lib.oracle_gaf_bucketed.argtypes = [c.c_void_p, c.c_int, c.c_size_t, c.c_int, c.c_double, c.c_int,
+                                        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     _lib = lib
     return lib
 
@@ -151,3 +159,48 @@ def pairwise(grads):
     if rc:
         raise RuntimeError("oracle_gaf_pairwise failed: %d" % rc)
     return D, G
+
+
+def best_seed(grads, tau):
+    """Order-indifferent variant. Returns (out, mask, dist, count, seed, counts_of_all_seeds)."""
+    grads, ptrs, P, code = _prep(grads)
+    N = len(grads)
+    out = np.empty(P, dtype=np.float64)
+    mask = np.zeros(N, dtype=np.uint8)
+    dist = np.zeros(N, dtype=np.float64)
+    counts = np.zeros(N, dtype=np.int32)
+    count, seed = ctypes.c_int32(0), ctypes.c_int32(-1)
+    rc = _load().oracle_gaf_best_seed(ptrs, N, P, code, float(tau), out.ctypes.data, mask.ctypes.data,
+                                      dist.ctypes.data, ctypes.addressof(count), ctypes.addressof(seed),
+                                      counts.ctypes.data)
+    if rc:
+        raise RuntimeError("oracle_gaf_best_seed failed: %d" % rc)
+    return out, mask, dist, int(count.value), int(seed.value), counts
+
+
+def sgd_step(theta, v, g_gaf, count, lr, mu, wd):
+    """GAF-SGD step on float64 arrays, in place (skipped when count == 1)."""
+    for a in (theta, v, g_gaf):
+        if a.dtype != np.float64 or not a.flags.c_contiguous or a.size != theta.size:
+            raise ValueError("theta, v, g_gaf must be contiguous float64 of one length")
+    rc = _load().oracle_sgd_step(theta.ctypes.data, v.ctypes.data, g_gaf.ctypes.data, int(count),
+                                 theta.size, float(lr), float(mu), float(wd))
+    if rc:
+        raise RuntimeError("oracle_sgd_step failed: %d" % rc)
+
+
+def bucketed(grads, tau, offsets):
+    """Independent filter per bucket. Returns (out[P], mask[B,N], dist[B,N], count[B])."""
+    grads, ptrs, P, code = _prep(grads)
+    N = len(grads)
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    B = off.size - 1
+    out = np.empty(P, dtype=np.float64)
+    mask = np.zeros((B, N), dtype=np.uint8)
+    dist = np.zeros((B, N), dtype=np.float64)
+    count = np.zeros(B, dtype=np.int32)
+    rc = _load().oracle_gaf_bucketed(ptrs, N, P, code, float(tau), B, off.ctypes.data, out.ctypes.data,
+                                     mask.ctypes.data, dist.ctypes.data, count.ctypes.data)
+    if rc:
+        raise RuntimeError("oracle_gaf_bucketed failed: %d" % rc)
+    return out, mask, dist, count

@@ -254,9 +254,13 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
                 add4(v0);
             }
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                *reinterpret_cast<float4 *>(out + base + size_t(u) * kBlock * 4) =
-                    make_float4(sum[u].x * inv_c, sum[u].y * inv_c, sum[u].z * inv_c, sum[u].w * inv_c);
+            for (int u = 0; u < kUnroll; ++u) {
+                const f32x4_t o = {sum[u].x * inv_c, sum[u].y * inv_c, sum[u].z * inv_c, sum[u].w * inv_c};
+                f32x4_t *dst = reinterpret_cast<f32x4_t *>(out + base + size_t(u) * kBlock * 4);
+                // out-of-cache sizes: the result is written once and not read back here (+5 % measured)
+                if (kStream) __builtin_nontemporal_store(o, dst);
+                else *dst = o;
+            }
         } else {
             // ragged last tile, element-wise
             for (int u = 0; u < kUnroll; ++u)
