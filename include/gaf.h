@@ -194,6 +194,66 @@ gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N
                                    uint8_t *accept_mask, float *cos_dist, int32_t *count, void *stream);
 
 /*
+ * Order-indifferent variant the paper sketches for the filter's dependence on
+ * the seed (Sec. 3.1, last paragraph; "Order Indifference" under future
+ * research): every micro-gradient takes a turn as the seed, the others being
+ * visited in ring order behind it (s, s+1, .., N-1, 0, .., s-1), and the run
+ * with the largest agreement is kept. Readings taken: agreement = number of
+ * accepted gradients; ties go to the lowest seed index. All N runs are replayed
+ * on one Gram matrix, so the cost is that of the Gram-first batch call.
+ *   accept_mask, cos_dist  indexed by gradient: mask[i], and the distance of
+ *                          g_i when the winning run visited it (0 for its seed).
+ *   seed                   DEVICE, one int32: index of the winning seed.
+ * 1 <= N <= 64 (GAF_EUNSUPPORTED beyond); other arguments as in gaf_aggregate.
+ */
+gaf_status gaf_aggregate_best_seed(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                   gaf_dtype dt, float tau, float *out, uint8_t *accept_mask,
+                                   float *cos_dist, int32_t *count, int32_t *seed, void *stream);
+
+/*
+ * Batch aggregation fused with the GAF-SGD update (Algorithm 1's last lines,
+ * Eq. 6) in the form of the optimizer the experiments name (Sec. 4.1: SGD with
+ * momentum and an L2 weight decay; heavy-ball form, no dampening, no Nesterov):
+ *     if c > 1:  d = g_GAF + weight_decay * params
+ *                momentum_buf <- momentum * momentum_buf + d
+ *                params <- params - lr * momentum_buf
+ *     if c == 1: no two micro-gradients agreed -- params and momentum_buf are
+ *                left bit-for-bit untouched (the paper's skipped step).
+ * The update runs inside the pass that forms g_GAF, so it costs one read and
+ * one write of params and momentum_buf and no pass of its own.
+ *   params, momentum_buf  DEVICE, P binary32 each, in/out, 16-byte aligned,
+ *                         distinct from each other, from out and from the inputs;
+ *                         momentum_buf starts at zero before the first step.
+ *   out                   DEVICE, P binary32, may be NULL: g_GAF (written also
+ *                         when the step is skipped).
+ * 1 <= N <= 64 (GAF_EUNSUPPORTED beyond); other arguments as in gaf_aggregate.
+ */
+gaf_status gaf_aggregate_sgd(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                             float tau, float *params, float *momentum_buf, float lr, float momentum,
+                             float weight_decay, float *out, uint8_t *accept_mask, float *cos_dist,
+                             int32_t *count, void *stream);
+
+/*
+ * Bucketed filtering ("cosine distance to buckets at a time", future research):
+ * the parameter vector is cut into B contiguous buckets -- layers, or the
+ * buckets of a gradient exchange -- and Algorithm 1 runs independently inside
+ * each, with its own mask, distances and count.
+ *   bucket_offsets  HOST array of B+1 element offsets, [0] = 0, [B] = P,
+ *                   strictly increasing, every offset a multiple of 8 elements
+ *                   (GAF_EALIGN otherwise) so that every slice stays 16-byte aligned.
+ *   out             DEVICE, P binary32: per-bucket g_GAF, concatenated.
+ *   accept_mask     DEVICE, B*N bytes, row b = bucket b.
+ *   cos_dist        DEVICE, B*N binary32, row b = bucket b.
+ *   count           DEVICE, B int32.
+ * Each bucket is one batch call under the context's schedule, enqueued in
+ * bucket order on `stream`.
+ */
+gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                  gaf_dtype dt, float tau, int B, const size_t *bucket_offsets,
+                                  float *out, uint8_t *accept_mask, float *cos_dist, int32_t *count,
+                                  void *stream);
+
+/*
  * Launch timing, for benchmarks (not part of the paper's method). Between
  * gaf_profile_begin and gaf_profile_end every kernel the context enqueues is
  * bracketed by a pair of HIP events on the call's stream (up to max_launches

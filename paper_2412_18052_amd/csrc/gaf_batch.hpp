@@ -19,24 +19,26 @@ namespace gaf {
 
 constexpr int kBatchMaxN = 64;   // gradients the Gram-first schedule handles (one Gram launch)
 
-// One wavefront. Visits g_2..g_N in order exactly as Algorithm 1 does, with the
-// three sums of Eq. 4 taken from the Gram matrix. Lane k carries the k-th
-// accepted index; the dot product is a fixed-tree wavefront sum.
-// Runs on ONE full wavefront (all 64 lanes active).
-__device__ __forceinline__ void run_filter(const double *gram, int N, float tau, State *st,
-                                           uint8_t *mask, float *cos_dist, int32_t *count,
-                                           int32_t *accepted_list)
+// One wavefront. Visits the gradients in ring order behind the seed
+// (seed, seed+1, .., N-1, 0, .., seed-1; seed = 0 is the plain array order)
+// exactly as Algorithm 1 does, with the three sums of Eq. 4 taken from the
+// Gram matrix. Lane k carries the k-th accepted index; the dot product is a
+// fixed-tree wavefront sum. Outputs are indexed by gradient index.
+// Runs on ONE full wavefront (all 64 lanes active). Returns c.
+__device__ __forceinline__ int run_filter(const double *gram, int N, int seed, float tau,
+                                          uint8_t *mask, float *cos_dist, int32_t *accepted_list)
 {
     const int lane = threadIdx.x & 63;
-    int my_index = lane == 0 ? 0 : -1;      // lane k < c holds the k-th accepted gradient
+    int my_index = lane == 0 ? seed : -1;   // lane k < c holds the k-th accepted gradient
     int c = 1;
-    double nn_g = gram[0];                  // |running sum|^2
+    double nn_g = gram[size_t(seed) * N + seed];   // |running sum|^2
     if (lane == 0) {
-        mask[0] = 1;
-        cos_dist[0] = 0.f;
-        accepted_list[0] = 0;
+        mask[seed] = 1;
+        cos_dist[seed] = 0.f;
+        accepted_list[0] = seed;
     }
-    for (int i = 1; i < N; ++i) {
+    for (int k = 1; k < N; ++k) {
+        const int i = seed + k < N ? seed + k : seed + k - N;
         const double term = my_index >= 0 ? gram[size_t(my_index) * N + i] : 0.0;
         const double dot = wave_sum(term);
         const double nn_i = gram[size_t(i) * N + i];
@@ -53,7 +55,15 @@ __device__ __forceinline__ void run_filter(const double *gram, int N, float tau,
             ++c;
         }
     }
-    if (lane == 0) {
+    return c;
+}
+
+__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
+                                                    uint8_t *mask, float *cos_dist, int32_t *count,
+                                                    int32_t *accepted_list)
+{
+    const int c = run_filter(gram, N, 0, tau, mask, cos_dist, accepted_list);
+    if (threadIdx.x == 0) {
         count[0] = c;
         st->count = c;
         st->accept = 0;
@@ -61,11 +71,44 @@ __device__ __forceinline__ void run_filter(const double *gram, int N, float tau,
     }
 }
 
-__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
-                                                    uint8_t *mask, float *cos_dist, int32_t *count,
-                                                    int32_t *accepted_list)
+// Order-indifferent variant (Sec. 3.1, last paragraph): workgroup s replays the
+// filter with g_s as the seed and the others in ring order behind it, all from
+// the same Gram matrix; results go to per-seed rows of a workspace.
+struct SeedWs {
+    uint8_t mask[kBatchMaxN][kBatchMaxN];
+    float dist[kBatchMaxN][kBatchMaxN];
+    int32_t list[kBatchMaxN][kBatchMaxN];
+    int32_t count[kBatchMaxN];
+};
+
+__global__ __launch_bounds__(64) void seed_runs_kernel(const double *gram, int N, float tau, SeedWs *ws)
 {
-    run_filter(gram, N, tau, st, mask, cos_dist, count, accepted_list);
+    const int s = blockIdx.x;
+    const int c = run_filter(gram, N, s, tau, ws->mask[s], ws->dist[s], ws->list[s]);
+    if (threadIdx.x == 0) ws->count[s] = c;
+}
+
+// Keeps the run with the most accepted gradients (ties: the lowest seed index).
+__global__ __launch_bounds__(64) void seed_select_kernel(const SeedWs *ws, int N, State *st, uint8_t *mask,
+                                                         float *cos_dist, int32_t *count, int32_t *seed_out,
+                                                         int32_t *accepted_list)
+{
+    int best = 0;
+    for (int s = 1; s < N; ++s)
+        if (ws->count[s] > ws->count[best]) best = s;
+    const int i = threadIdx.x;
+    if (i < N) {
+        mask[i] = ws->mask[best][i];
+        cos_dist[i] = ws->dist[best][i];
+        accepted_list[i] = ws->list[best][i];
+    }
+    if (i == 0) {
+        count[0] = ws->count[best];
+        seed_out[0] = best;
+        st->count = ws->count[best];
+        st->accept = 0;
+        st->seed = 0;
+    }
 }
 
 // ---- small batches (N <= 8): inner products on the vector ALU in binary64 ----
@@ -193,13 +236,30 @@ struct MeanArgs {
     int N;
     const int32_t *accepted_list;   // DEVICE, indices of the accepted gradients in visiting order
     const State *st;                // st->count = c
-    float *out;
+    float *out;                     // may be NULL in the fused-optimizer form
     size_t P;
+    // fused GAF-SGD step (kSgd): parameters and momentum buffer, in place
+    float *theta, *vel;
+    float lr, mu, wd;
 };
+
+// The optimizer step the experiments use (Sec. 4.1: SGD with momentum, weight
+// decay as L2 term) applied to one element of the macro-gradient g (Eq. 6):
+//     d = g + wd * theta;  v <- mu * v + d;  theta <- theta - lr * v
+__device__ __forceinline__ void sgd_element(float g, float &theta, float &v, float lr, float mu, float wd)
+{
+    const float d = __builtin_fmaf(wd, theta, g);
+    v = __builtin_fmaf(mu, v, d);
+    theta = __builtin_fmaf(-lr, v, theta);
+}
 
 // Eq. 5: out = (sum of the accepted gradients) / c, accumulated in binary32 in
 // visiting order. Reads c gradients once, writes the result once.
-template <typename T, bool kStream>
+// kSgd: the GAF-SGD update is applied in the same pass (one read and one write
+// of parameters and momentum, no separate optimizer pass); with c == 1 there is
+// no consensus and parameters and optimizer state are left untouched
+// (Algorithm 1's skip).
+template <typename T, bool kStream, bool kSgd>
 __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
 {
     __shared__ const void *table[kBatchMaxN];
@@ -218,6 +278,8 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
     const size_t P = a.P;
     const size_t ntiles = (P + kTile - 1) / kTile;
     float *out = a.out;
+    const bool step = kSgd && c > 1;
+    if (kSgd && !step && !out) return;      // skipped step, nothing else asked for
 
     for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const size_t base = t * kTile + size_t(threadIdx.x) * 4;
@@ -255,11 +317,27 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
+                const size_t idx = base + size_t(u) * kBlock * 4;
                 const f32x4_t o = {sum[u].x * inv_c, sum[u].y * inv_c, sum[u].z * inv_c, sum[u].w * inv_c};
-                f32x4_t *dst = reinterpret_cast<f32x4_t *>(out + base + size_t(u) * kBlock * 4);
-                // out-of-cache sizes: the result is written once and not read back here (+5 % measured)
-                if (kStream) __builtin_nontemporal_store(o, dst);
-                else *dst = o;
+                if (!kSgd || out) {
+                    f32x4_t *dst = reinterpret_cast<f32x4_t *>(out + idx);
+                    // out-of-cache sizes: the result is written once and not read back here (+5 % measured)
+                    if (kStream) __builtin_nontemporal_store(o, dst);
+                    else *dst = o;
+                }
+                if (step) {
+                    f32x4_t th = *reinterpret_cast<const f32x4_t *>(a.theta + idx);
+                    f32x4_t ve = *reinterpret_cast<const f32x4_t *>(a.vel + idx);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float t1 = th[e], v1 = ve[e];
+                        sgd_element(o[e], t1, v1, a.lr, a.mu, a.wd);
+                        th[e] = t1;
+                        ve[e] = v1;
+                    }
+                    *reinterpret_cast<f32x4_t *>(a.theta + idx) = th;
+                    *reinterpret_cast<f32x4_t *>(a.vel + idx) = ve;
+                }
             }
         } else {
             // ragged last tile, element-wise
@@ -269,7 +347,9 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
                     if (idx >= P) continue;
                     float sum = 0.f;
                     for (int k = 0; k < c; ++k) sum += load1(static_cast<const T *>(table[list[k]]), idx);
-                    out[idx] = sum * inv_c;
+                    const float o = sum * inv_c;
+                    if (!kSgd || out) out[idx] = o;
+                    if (step) sgd_element(o, a.theta[idx], a.vel[idx], a.lr, a.mu, a.wd);
                 }
         }
     }

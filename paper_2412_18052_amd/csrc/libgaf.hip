@@ -23,6 +23,7 @@ struct gaf_ctx {
     double *gram_ws;     // device, [kGramBlocks][kGramMaxTiles][kGramTile]
     double *gram_full;   // device, [max_N][max_N]
     int32_t *accepted;   // device, [max_N] indices of accepted gradients (Gram-first schedule)
+    SeedWs *seed_ws;     // device, per-seed filter runs (order-indifferent variant)
     gaf_schedule schedule;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
@@ -323,19 +324,39 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
     return launched();
 }
 
-// `gram` non-null: the caller's matrix of inner products is used and the Gram pass is skipped.
+// Variations of the Gram-first batch call.
+struct BatchOptions {
+    const double *gram = nullptr;   // caller's matrix of inner products: the Gram pass is skipped
+    int32_t *best_seed = nullptr;   // non-null: order-indifferent variant, receives the winning seed
+    float *theta = nullptr;         // non-null: fused GAF-SGD step on (theta, vel)
+    float *vel = nullptr;
+    float lr = 0.f, mu = 0.f, wd = 0.f;
+};
+
 template <typename T, bool kStream>
 gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P, float tau,
-                               const double *gram, float *out, uint8_t *mask, float *cos_dist,
+                               const BatchOptions &opt, float *out, uint8_t *mask, float *cos_dist,
                                int32_t *count, hipStream_t s)
 {
+    const double *gram = opt.gram;
     if (!gram) {
         const gaf_status rc = N <= kSmallMaxN ? gram_small<T, kStream>(ctx, grads, N, P, s)
                                               : gram_all_pairs<T>(ctx, grads, N, P, s);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     }
-    {
+    if (opt.best_seed) {
+        {
+            Timed t(ctx, s, GAF_K_FILTER);
+            seed_runs_kernel<<<N, 64, 0, s>>>(gram, N, tau, ctx->seed_ws);
+        }
+        if (launched() != GAF_OK) return GAF_EHIP;
+        {
+            Timed t(ctx, s, GAF_K_FILTER);
+            seed_select_kernel<<<1, 64, 0, s>>>(ctx->seed_ws, N, ctx->st, mask, cos_dist, count,
+                                                opt.best_seed, ctx->accepted);
+        }
+    } else {
         Timed t(ctx, s, GAF_K_FILTER);
         filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted);
     }
@@ -347,9 +368,17 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     m.st = ctx->st;
     m.out = out;
     m.P = P;
+    m.theta = opt.theta;
+    m.vel = opt.vel;
+    m.lr = opt.lr;
+    m.mu = opt.mu;
+    m.wd = opt.wd;
     {
         Timed t(ctx, s, GAF_K_MEAN);
-        mean_kernel<T, kStream><<<pass_blocks(P), kBlock, 0, s>>>(m);
+        if (opt.theta)
+            mean_kernel<T, kStream, true><<<pass_blocks(P), kBlock, 0, s>>>(m);
+        else
+            mean_kernel<T, kStream, false><<<pass_blocks(P), kBlock, 0, s>>>(m);
     }
     return launched();
 }
@@ -376,7 +405,7 @@ gaf_status pairwise_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t P
 }
 
 gaf_status gram_first_dispatch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
-                               float tau, const double *gram, float *out, uint8_t *mask,
+                               float tau, const BatchOptions &gram, float *out, uint8_t *mask,
                                float *cos_dist, int32_t *count, hipStream_t s)
 {
     // the masked mean reads up to N gradients of s bytes and writes 4 bytes per element
@@ -386,6 +415,42 @@ gaf_status gram_first_dispatch(gaf_ctx *ctx, const void *const *grads, int N, si
                   : aggregate_gram_impl<float, false>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s);
     return st ? aggregate_gram_impl<bf16_t, true>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s)
               : aggregate_gram_impl<bf16_t, false>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s);
+}
+
+// Schedule selection of the plain batch call (arguments already validated).
+gaf_status aggregate_dispatch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                              float tau, float *out, uint8_t *accept_mask, float *cos_dist,
+                              int32_t *count, hipStream_t s)
+{
+    if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
+    const bool gram_first = ctx->schedule == GAF_SCHEDULE_GRAM ||
+                            (ctx->schedule == GAF_SCHEDULE_AUTO && N >= 2 && N <= kBatchMaxN);
+    if (gram_first)
+        return gram_first_dispatch(ctx, grads, N, P, dt, tau, BatchOptions{}, out, accept_mask, cos_dist, count, s);
+    if (dt == GAF_F32)
+        return stream_loads(P, 4)
+                   ? aggregate_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+                   : aggregate_impl<float, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+    return stream_loads(P, 2)
+               ? aggregate_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
+               : aggregate_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+}
+
+// Checks shared by the batch entry points. `out` may be NULL where the caller allows it.
+gaf_status check_batch(const gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                       const float *out, bool out_required)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!grads || N < 1 || P == 0 || (out_required && !out)) return GAF_EINVAL;
+    if (N > ctx->max_N || P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (out && misaligned(out)) return GAF_EALIGN;
+    for (int i = 0; i < N; ++i) {
+        if (!grads[i] || (out && grads[i] == static_cast<const void *>(out))) return GAF_EINVAL;
+        if (misaligned(grads[i])) return GAF_EALIGN;
+    }
+    return GAF_OK;
 }
 
 }  // namespace
@@ -435,8 +500,9 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
                         sizeof(double) * 3 * kMaxBlocks) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->gram_ws), gram_ws_bytes) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->gram_full), gram_full_bytes) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void **>(&ctx->accepted), sizeof(int32_t) * size_t(max_N)) ==
-                  hipSuccess;
+              hipMalloc(reinterpret_cast<void **>(&ctx->accepted),
+                        sizeof(int32_t) * size_t(max_N < kBatchMaxN ? kBatchMaxN : max_N)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->seed_ws), sizeof(SeedWs)) == hipSuccess;
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -461,6 +527,7 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->gram_ws) (void)hipFree(ctx->gram_ws);
     if (ctx->gram_full) (void)hipFree(ctx->gram_full);
     if (ctx->accepted) (void)hipFree(ctx->accepted);
+    if (ctx->seed_ws) (void)hipFree(ctx->seed_ws);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;
@@ -518,19 +585,8 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
         if (!grads[i] || grads[i] == static_cast<const void *>(out)) return GAF_EINVAL;
         if (misaligned(grads[i])) return GAF_EALIGN;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
-    const bool gram_first = ctx->schedule == GAF_SCHEDULE_GRAM ||
-                            (ctx->schedule == GAF_SCHEDULE_AUTO && N >= 2 && N <= kBatchMaxN);
-    if (gram_first)
-        return gram_first_dispatch(ctx, grads, N, P, dt, tau, nullptr, out, accept_mask, cos_dist, count, s);
-    if (dt == GAF_F32)
-        return stream_loads(P, 4)
-                   ? aggregate_impl<float, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
-                   : aggregate_impl<float, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
-    return stream_loads(P, 2)
-               ? aggregate_impl<bf16_t, true>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s)
-               : aggregate_impl<bf16_t, false>(ctx, grads, N, P, tau, out, accept_mask, cos_dist, count, s);
+    return aggregate_dispatch(ctx, grads, N, P, dt, tau, out, accept_mask, cos_dist, count,
+                              static_cast<hipStream_t>(stream));
 }
 
 gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
@@ -549,8 +605,74 @@ gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N
         if (!grads[i] || grads[i] == static_cast<const void *>(out)) return GAF_EINVAL;
         if (misaligned(grads[i])) return GAF_EALIGN;
     }
-    return gram_first_dispatch(ctx, grads, N, P, dt, tau, gram, out, accept_mask, cos_dist, count,
+    BatchOptions opt;
+    opt.gram = gram;
+    return gram_first_dispatch(ctx, grads, N, P, dt, tau, opt, out, accept_mask, cos_dist, count,
                                static_cast<hipStream_t>(stream));
+}
+
+gaf_status gaf_aggregate_best_seed(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                   gaf_dtype dt, float tau, float *out, uint8_t *accept_mask,
+                                   float *cos_dist, int32_t *count, int32_t *seed, void *stream)
+{
+    gaf_status rc = check_batch(ctx, grads, N, P, dt, out, true);
+    if (rc != GAF_OK) return rc;
+    if (!accept_mask || !cos_dist || !count || !seed) return GAF_EINVAL;
+    if (N > kBatchMaxN) return GAF_EUNSUPPORTED;
+    BatchOptions opt;
+    opt.best_seed = seed;
+    return gram_first_dispatch(ctx, grads, N, P, dt, tau, opt, out, accept_mask, cos_dist, count,
+                               static_cast<hipStream_t>(stream));
+}
+
+gaf_status gaf_aggregate_sgd(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
+                             float tau, float *params, float *momentum_buf, float lr, float momentum,
+                             float weight_decay, float *out, uint8_t *accept_mask, float *cos_dist,
+                             int32_t *count, void *stream)
+{
+    gaf_status rc = check_batch(ctx, grads, N, P, dt, out, false);
+    if (rc != GAF_OK) return rc;
+    if (!params || !momentum_buf || !accept_mask || !cos_dist || !count) return GAF_EINVAL;
+    if (params == momentum_buf || params == out || momentum_buf == out) return GAF_EINVAL;
+    if (misaligned(params) || misaligned(momentum_buf)) return GAF_EALIGN;
+    for (int i = 0; i < N; ++i)
+        if (grads[i] == static_cast<const void *>(params) || grads[i] == static_cast<const void *>(momentum_buf))
+            return GAF_EINVAL;
+    if (N > kBatchMaxN) return GAF_EUNSUPPORTED;
+    BatchOptions opt;
+    opt.theta = params;
+    opt.vel = momentum_buf;
+    opt.lr = lr;
+    opt.mu = momentum;
+    opt.wd = weight_decay;
+    return gram_first_dispatch(ctx, grads, N, P, dt, tau, opt, out, accept_mask, cos_dist, count,
+                               static_cast<hipStream_t>(stream));
+}
+
+gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                  gaf_dtype dt, float tau, int B, const size_t *bucket_offsets,
+                                  float *out, uint8_t *accept_mask, float *cos_dist, int32_t *count,
+                                  void *stream)
+{
+    gaf_status rc = check_batch(ctx, grads, N, P, dt, out, true);
+    if (rc != GAF_OK) return rc;
+    if (!accept_mask || !cos_dist || !count || B < 1 || !bucket_offsets) return GAF_EINVAL;
+    if (bucket_offsets[0] != 0 || bucket_offsets[B] != P) return GAF_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        if (bucket_offsets[b + 1] <= bucket_offsets[b]) return GAF_EINVAL;
+        if (bucket_offsets[b] % 8 != 0) return GAF_EALIGN;   // keeps every slice 16-byte aligned
+    }
+    if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
+    const size_t es = dt == GAF_F32 ? 4 : 2;
+    std::vector<const void *> slice(static_cast<size_t>(N));
+    for (int b = 0; b < B; ++b) {
+        const size_t lo = bucket_offsets[b], len = bucket_offsets[b + 1] - lo;
+        for (int i = 0; i < N; ++i) slice[i] = static_cast<const char *>(grads[i]) + lo * es;
+        rc = aggregate_dispatch(ctx, slice.data(), N, len, dt, tau, out + lo, accept_mask + size_t(b) * N,
+                                cos_dist + size_t(b) * N, count + b, static_cast<hipStream_t>(stream));
+        if (rc != GAF_OK) return rc;
+    }
+    return GAF_OK;
 }
 
 gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule)

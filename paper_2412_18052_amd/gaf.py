@@ -16,7 +16,8 @@ GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEV
 GAF_F32, GAF_BF16 = 0, 1
 
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
-           "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram")
+           "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram",
+           "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -67,6 +68,17 @@ def load(path=None):
     lib.gaf_aggregate_with_gram.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
                                             c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
                                             c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_aggregate_best_seed.restype = c.c_int
+    lib.gaf_aggregate_best_seed.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
+                                            c.c_int, c.c_float] + [c.c_void_p] * 6
+    lib.gaf_aggregate_sgd.restype = c.c_int
+    lib.gaf_aggregate_sgd.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
+                                      c.c_float, c.c_void_p, c.c_void_p, c.c_float, c.c_float,
+                                      c.c_float] + [c.c_void_p] * 5
+    lib.gaf_aggregate_bucketed.restype = c.c_int
+    lib.gaf_aggregate_bucketed.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
+                                           c.c_int, c.c_float, c.c_int, c.POINTER(c.c_size_t)] + \
+                                          [c.c_void_p] * 5
     lib.gaf_set_schedule.restype = c.c_int
     lib.gaf_set_schedule.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_begin.restype = c.c_int
@@ -191,6 +203,59 @@ def gaf_aggregate_with_gram(ctx, grads, tau, gram, out=None, accept_mask=None, c
     _check(load().gaf_aggregate_with_gram(ctx.handle, table, N, P, code, float(tau), _ptr(gram),
                                           _ptr(out), _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
                                           _stream_handle(stream)), "gaf_aggregate_with_gram")
+    return out, accept_mask, cos_dist, count
+
+
+def _batch_outputs(grads, rows, out, accept_mask, cos_dist, count):
+    P, N, dev = grads[0].numel(), len(grads), grads[0].device
+    out = torch.empty(P, dtype=torch.float32, device=dev) if out is None else out
+    shape = (N,) if rows is None else (rows, N)
+    accept_mask = torch.empty(shape, dtype=torch.uint8, device=dev) if accept_mask is None else accept_mask
+    cos_dist = torch.empty(shape, dtype=torch.float32, device=dev) if cos_dist is None else cos_dist
+    count = torch.empty(1 if rows is None else rows, dtype=torch.int32, device=dev) if count is None else count
+    return out, accept_mask, cos_dist, count
+
+
+def gaf_aggregate_best_seed(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,
+                            seed=None, stream=None):
+    """Order-indifferent variant. Returns (out, accept_mask, cos_dist, count, seed)."""
+    table, P, code = _grad_table(grads)
+    out, accept_mask, cos_dist, count = _batch_outputs(grads, None, out, accept_mask, cos_dist, count)
+    seed = torch.empty(1, dtype=torch.int32, device=grads[0].device) if seed is None else seed
+    _check(load().gaf_aggregate_best_seed(ctx.handle, table, len(grads), P, code, float(tau), _ptr(out),
+                                          _ptr(accept_mask), _ptr(cos_dist), _ptr(count), _ptr(seed),
+                                          _stream_handle(stream)), "gaf_aggregate_best_seed")
+    return out, accept_mask, cos_dist, count, seed
+
+
+def gaf_aggregate_sgd(ctx, grads, tau, params, momentum_buf, lr, momentum, weight_decay, out=None,
+                      accept_mask=None, cos_dist=None, count=None, want_out=True, stream=None):
+    """Aggregation fused with the GAF-SGD step on (params, momentum_buf), in place.
+    Returns (out or None, accept_mask, cos_dist, count)."""
+    table, P, code = _grad_table(grads)
+    for t in (params, momentum_buf):
+        if t.dtype != torch.float32 or t.numel() != P or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("params and momentum_buf must be contiguous float32 device tensors of length P")
+    o, accept_mask, cos_dist, count = _batch_outputs(grads, None, out if want_out else params[:0],
+                                                     accept_mask, cos_dist, count)
+    o = o if want_out else None
+    _check(load().gaf_aggregate_sgd(ctx.handle, table, len(grads), P, code, float(tau), _ptr(params),
+                                    _ptr(momentum_buf), float(lr), float(momentum), float(weight_decay),
+                                    _ptr(o), _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
+                                    _stream_handle(stream)), "gaf_aggregate_sgd")
+    return o, accept_mask, cos_dist, count
+
+
+def gaf_aggregate_bucketed(ctx, grads, tau, bucket_offsets, out=None, accept_mask=None, cos_dist=None,
+                           count=None, stream=None):
+    """Independent filter per bucket. Returns (out[P], accept_mask[B,N], cos_dist[B,N], count[B])."""
+    table, P, code = _grad_table(grads)
+    B = len(bucket_offsets) - 1
+    out, accept_mask, cos_dist, count = _batch_outputs(grads, B, out, accept_mask, cos_dist, count)
+    offs = (ctypes.c_size_t * (B + 1))(*[int(x) for x in bucket_offsets])
+    _check(load().gaf_aggregate_bucketed(ctx.handle, table, len(grads), P, code, float(tau), B, offs,
+                                         _ptr(out), _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
+                                         _stream_handle(stream)), "gaf_aggregate_bucketed")
     return out, accept_mask, cos_dist, count
 
 

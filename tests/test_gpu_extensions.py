@@ -1,0 +1,171 @@
+"""GPU parity of the follow-on entry points against the oracle: order-indifferent
+seed choice, fused GAF-SGD step, bucketed filtering. Same bars as the main
+parity tests; parameters and momentum within 1e-6 relative L2 (three binary32
+FMAs per element on a macro-gradient that is itself within 1e-5)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from conftest import MARGIN, oracle_arrays
+from paper_2412_18052_amd import gaf
+from paper_2412_18052_amd import workloads as wl
+from test_gpu_parity import DIST_ATOL, OUT_RTOL, check_against_oracle, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", params=["sequential", "auto"])
+def ctx(request):
+    c = gaf.gaf_create(max_P=1 << 28, max_N=128)
+    gaf.gaf_set_schedule(c, request.param)
+    yield c
+    torch.cuda.synchronize()
+    gaf.gaf_destroy(c)
+
+
+def ring_workload(oracle, name, P, N, seed0=0):
+    """Workload whose every ring rotation keeps the margin to tau (so every seed's run is robust)."""
+    for seed in range(seed0, seed0 + 16):
+        w, grads = wl.generate(name, seed, P=P, N=N)
+        a = oracle_arrays(grads)
+        tau = np.float32(w.tau)
+        ok = True
+        for s in range(N):
+            _, _, d, _ = oracle.aggregate([a[(s + k) % N] for k in range(N)], tau)
+            ok = ok and bool(np.all(np.abs(d[1:] - float(tau)) >= MARGIN))
+        if ok:
+            return w, grads, a
+    raise RuntimeError("no seed keeps the margin on every rotation")
+
+
+# ------------------------------------------------------------ best seed -----
+def test_best_seed_orthogonal_seed(ctx, oracle):
+    P = 60_001
+    g = torch.Generator().manual_seed(5)
+    common = torch.zeros(P); common[1000:] = torch.randn(P - 1000, generator=g)
+    seed = torch.zeros(P); seed[:1000] = torch.randn(1000, generator=g)
+    grads = [seed] + [common + 0.3 * torch.cat([torch.zeros(1000), torch.randn(P - 1000, generator=g)])
+                      for _ in range(3)]
+    a = oracle_arrays(grads)
+    ref = oracle.best_seed(a, np.float32(0.5))
+    assert ref[3] == 3 and ref[4] == 1                      # the plain filter would stop at c = 1
+    out, mask, dist, count, sd = gaf.gaf_aggregate_best_seed(ctx, [x.cuda() for x in grads], 0.5)
+    check_against_oracle((out, mask, dist, count), ref[:4], "f32")
+    assert int(sd.item()) == ref[4]
+    plain = gaf.gaf_aggregate(ctx, [x.cuda() for x in grads], 0.5)
+    torch.cuda.synchronize()
+    assert int(plain[3].item()) == 1
+
+
+@pytest.mark.parametrize("name,P,N,dtype", [("streaming", 120_007, 9, "f32"), ("large", 200_003, 16, "bf16"),
+                                            ("resnet18", 50_001, 5, "f32"), ("diagnostic", 80_009, 64, "f32"),
+                                            ("tiny", 33_001, 1, "f32")])
+def test_best_seed_parity(ctx, oracle, name, P, N, dtype):
+    w, grads, a = ring_workload(oracle, name, P, N)
+    ref = oracle.best_seed(a, np.float32(w.tau))
+    out, mask, dist, count, sd = gaf.gaf_aggregate_best_seed(ctx, [x.cuda() for x in grads], w.tau)
+    check_against_oracle((out, mask, dist, count), ref[:4], dtype)
+    assert int(sd.item()) == ref[4]
+
+
+# -------------------------------------------------------------- GAF-SGD -----
+@pytest.mark.parametrize("name,P,N,dtype", [("resnet18", 300_007, 8, "f32"), ("large", 250_001, 16, "bf16"),
+                                            ("tiny", 70_003, 2, "f32")])
+def test_sgd_step_parity(ctx, oracle, name, P, N, dtype):
+    from conftest import workload_with_margin
+    w, grads, ref = workload_with_margin(name, P=P, N=N)
+    dev = [x.cuda() for x in grads]
+    g = torch.Generator().manual_seed(11)
+    theta0 = torch.randn(w.P, generator=g); theta = theta0.cuda(); vel = torch.zeros(w.P, device="cuda")
+    th64 = theta0.numpy().astype(np.float64); v64 = np.zeros(w.P)
+    lr, mu, wd = 0.01, 0.9, 0.01                            # the paper's recipe (Sec. 4.1)
+    for it in range(2):                                     # second step exercises the momentum term
+        out, mask, dist, count = gaf.gaf_aggregate_sgd(ctx, dev, w.tau, theta, vel, lr, mu, wd,
+                                                       want_out=(it == 0))
+        oracle.sgd_step(th64, v64, ref[0], ref[3], np.float32(lr), np.float32(mu), np.float32(wd))
+        torch.cuda.synchronize()
+        assert mask.cpu().numpy().tolist() == ref[1].tolist() and int(count.item()) == ref[3]
+        assert np.max(np.abs(dist.cpu().numpy().astype(np.float64) - ref[2])) <= DIST_ATOL
+        if it == 0:
+            assert rel_l2(out.cpu().numpy(), ref[0]) <= OUT_RTOL[dtype]
+        else:
+            assert out is None
+        tol = 1e-6 if dtype == "f32" else 2e-3
+        assert rel_l2(theta.cpu().numpy(), th64) <= tol
+        assert rel_l2(vel.cpu().numpy(), v64) <= max(tol, 1e-6)
+    assert ref[3] > 1
+
+
+def test_sgd_step_skipped_without_consensus(ctx, oracle):
+    w, grads = wl.generate("resnet18", 1, P=90_001)
+    dev = [x.cuda() for x in grads]
+    theta0 = torch.randn(w.P, generator=torch.Generator().manual_seed(3))
+    vel0 = torch.randn(w.P, generator=torch.Generator().manual_seed(4))
+    theta = theta0.cuda(); vel = vel0.cuda()
+    out, mask, dist, count = gaf.gaf_aggregate_sgd(ctx, dev, -1.0, theta, vel, 0.1, 0.9, 0.01)
+    torch.cuda.synchronize()
+    assert int(count.item()) == 1 and mask.cpu().tolist() == [1] + [0] * (w.N - 1)
+    assert torch.equal(theta.cpu(), theta0) and torch.equal(vel.cpu(), vel0)     # bit for bit
+    assert torch.equal(out.cpu(), grads[0])
+    out, mask, dist, count = gaf.gaf_aggregate_sgd(ctx, dev, -1.0, theta, vel, 0.1, 0.9, 0.01, want_out=False)
+    torch.cuda.synchronize()
+    assert out is None and torch.equal(theta.cpu(), theta0) and torch.equal(vel.cpu(), vel0)
+    # plain gradient step (mu = wd = 0, everything admitted): theta - lr * mean (Eq. 2, Eq. 6)
+    out, mask, dist, count = gaf.gaf_aggregate_sgd(ctx, dev, 2.0, theta, vel, 0.5, 0.0, 0.0)
+    torch.cuda.synchronize()
+    mean = oracle.plain_average(oracle_arrays(grads))
+    assert rel_l2(theta.cpu().numpy(), theta0.numpy().astype(np.float64) - 0.5 * mean) <= 1e-6
+
+
+# ------------------------------------------------------------- bucketed -----
+@pytest.mark.parametrize("name,P,N,dtype", [("resnet18", 400_003, 8, "f32"), ("large", 300_017, 16, "bf16"),
+                                            ("streaming", 200_001, 70, "f32")])
+def test_bucketed_parity(ctx, oracle, name, P, N, dtype):
+    offs = [0, 8, 4096, 16_384 + 8, 100_000, 200_000 - 8, P]
+    offs = sorted(set(o for o in offs if o <= P))
+    for seed in range(16):
+        w, grads = wl.generate(name, seed, P=P, N=N)
+        a = oracle_arrays(grads)
+        ref = oracle.bucketed(a, np.float32(w.tau), offs)
+        if np.all(np.abs(ref[2][:, 1:] - float(np.float32(w.tau))) >= MARGIN):
+            break
+    else:
+        raise RuntimeError("no seed keeps the margin in every bucket")
+    out, mask, dist, count = gaf.gaf_aggregate_bucketed(ctx, [x.cuda() for x in grads], w.tau, offs)
+    torch.cuda.synchronize()
+    assert mask.cpu().numpy().tolist() == ref[1].tolist()
+    assert count.cpu().numpy().tolist() == ref[3].tolist()
+    assert np.max(np.abs(dist.cpu().numpy().astype(np.float64) - ref[2])) <= DIST_ATOL
+    o = out.cpu().numpy()
+    for b in range(len(offs) - 1):
+        assert rel_l2(o[offs[b]:offs[b + 1]], ref[0][offs[b]:offs[b + 1]]) <= OUT_RTOL[dtype]
+    assert len(set(map(tuple, ref[1].tolist()))) >= 1
+
+
+def test_extension_argument_errors(ctx):
+    lib = gaf.load()
+    P = 4096
+    x = torch.randn(P, device="cuda"); out = torch.empty(P, device="cuda")
+    th = torch.zeros(P, device="cuda"); ve = torch.zeros(P, device="cuda")
+    mask = torch.empty(4 * 80, dtype=torch.uint8, device="cuda"); dist = torch.empty(4 * 80, device="cuda")
+    count = torch.zeros(4, dtype=torch.int32, device="cuda"); seed = torch.zeros(1, dtype=torch.int32, device="cuda")
+    xp = x.data_ptr()
+    t2 = (ctypes.c_void_p * 2)(xp, xp); t65 = (ctypes.c_void_p * 65)(*([xp] * 65))
+    m, d, c = mask.data_ptr(), dist.data_ptr(), count.data_ptr()
+    assert lib.gaf_aggregate_best_seed(ctx.handle, t65, 65, P, 0, 1.0, out.data_ptr(), m, d, c, seed.data_ptr(), None) == gaf.GAF_EUNSUPPORTED
+    assert lib.gaf_aggregate_best_seed(ctx.handle, t2, 2, P, 0, 1.0, out.data_ptr(), m, d, c, None, None) == gaf.GAF_EINVAL
+    assert lib.gaf_aggregate_sgd(ctx.handle, t2, 2, P, 0, 1.0, th.data_ptr(), th.data_ptr(), 0.1, 0.9, 0.0, None, m, d, c, None) == gaf.GAF_EINVAL
+    assert lib.gaf_aggregate_sgd(ctx.handle, t2, 2, P, 0, 1.0, th.data_ptr() + 4, ve.data_ptr(), 0.1, 0.9, 0.0, None, m, d, c, None) == gaf.GAF_EALIGN
+    assert lib.gaf_aggregate_sgd(ctx.handle, t2, 2, P, 0, 1.0, xp, ve.data_ptr(), 0.1, 0.9, 0.0, None, m, d, c, None) == gaf.GAF_EINVAL
+
+    def buck(offs):
+        arr = (ctypes.c_size_t * len(offs))(*offs)
+        return lib.gaf_aggregate_bucketed(ctx.handle, t2, 2, P, 0, 1.0, len(offs) - 1, arr, out.data_ptr(), m, d, c, None)
+    assert buck([0, 1024, P]) == gaf.GAF_OK
+    assert buck([0, 1023, P]) == gaf.GAF_EALIGN
+    assert buck([0, 2048, 2048, P]) == gaf.GAF_EINVAL
+    assert buck([8, P]) == gaf.GAF_EINVAL
+    assert buck([0, P - 8]) == gaf.GAF_EINVAL
+    torch.cuda.synchronize()
