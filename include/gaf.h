@@ -157,8 +157,9 @@ gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule);
  *   cos_dist_out  DEVICE, one binary32, may be NULL: D_i.
  *   accepted_out  DEVICE, one byte, may be NULL: 1 if accepted.
  *
- * Three kernels: the distance reduction, a one-workgroup decision kernel, then
- * the conditional update, which exits at once when g_i was rejected.
+ * Two kernels: the distance reduction, then decision and conditional update in
+ * one launch (every workgroup re-derives the decision from the partial sums; a
+ * rejected g_i costs no further memory traffic).
  */
 gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                     gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,

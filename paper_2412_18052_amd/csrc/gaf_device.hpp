@@ -15,7 +15,7 @@ struct State {
     int32_t accept;    // 1 if the gradient reduced last was accepted
     int32_t count;     // c of Algorithm 1 including that gradient
     int32_t seed;      // 1 if that gradient is the seed (aggregate <- g_i)
-    int32_t pad_;
+    int32_t c_prev;    // streaming: c before the gradient being visited (stashed by the reducing pass)
     double dot, nn_g, nn_i;  // the three sums behind the last distance
 };
 

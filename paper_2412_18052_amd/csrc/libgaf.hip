@@ -38,10 +38,10 @@ inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 
 // Workgroups for a streaming pass over P elements: every workgroup gets the
 // same number of tiles (to within one), at most kMaxBlocks workgroups.
-inline int pass_blocks(size_t P)
+inline int pass_blocks(size_t P, int cap = kMaxBlocks)
 {
     const size_t ntiles = (P + kTile - 1) / kTile;
-    const size_t iters = (ntiles + kMaxBlocks - 1) / kMaxBlocks;
+    const size_t iters = (ntiles + cap - 1) / cap;
     return static_cast<int>((ntiles + iters - 1) / iters);
 }
 
@@ -177,7 +177,7 @@ template <typename T, bool kStream>
 gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                      float tau, float *cos_out, uint8_t *acc_out, hipStream_t s)
 {
-    const dim3 grid(pass_blocks(P)), block(kBlock);
+    const dim3 grid(pass_blocks(P, kStepBlocks)), block(kBlock);
     PassArgs a{};
     a.P = P;
     a.st = ctx->st;
@@ -187,27 +187,20 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
     a.dst = accum;
     a.next = g_i;
     a.count_in = count;
-    a.cos_out = cos_out;
-    a.mask_out = acc_out;
     {
         Timed t(ctx, s, GAF_K_REDUCE);
         reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
-    {
-        Timed t(ctx, s, GAF_K_DECIDE);
-        decide_kernel<<<1, block, 0, s>>>(a, grid.x);
-    }
-    if (launched() != GAF_OK) return GAF_EHIP;
     a.pend = g_i;
     a.next = nullptr;
     a.count_in = nullptr;
-    a.cos_out = nullptr;
-    a.mask_out = nullptr;
+    a.cos_out = cos_out;
+    a.mask_out = acc_out;
     a.count_out = count;
     {
         Timed t(ctx, s, GAF_K_UPDATE);
-        update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+        decide_update_kernel<T, kStream><<<grid, block, 0, s>>>(a, grid.x);
     }
     return launched();
 }
