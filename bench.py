@@ -58,6 +58,8 @@ def main():
                     choices=["tiny", "resnet18", "streaming", "large", "diagnostic"])
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "gram"],
                     help="schedule of the batch call (auto = Gram-first for N <= 64)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (launch-bound sizes)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--P", type=int, default=None, help="override the vector length")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
@@ -130,11 +132,25 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # the library neither allocates nor synchronises in its calls, so a step can be captured
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(args.steps):
-        step()
+        run_step()
     ev1.record()
     torch.cuda.synchronize()
     wall_s = time.perf_counter() - t0
@@ -303,7 +319,7 @@ def main():
                         % w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau,
-                   "mode": w.mode, "schedule": schedule_used, "seed": args.seed, "accepted": c_h,
+                   "mode": w.mode, "schedule": schedule_used, "hip_graph": bool(args.graph), "seed": args.seed, "accepted": c_h,
                    "algorithmic_bytes_per_step": step_bytes,
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,

@@ -169,3 +169,44 @@ def test_extension_argument_errors(ctx):
     assert buck([8, P]) == gaf.GAF_EINVAL
     assert buck([0, P - 8]) == gaf.GAF_EINVAL
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------ HIP graphs -----
+def test_calls_can_be_captured_in_a_graph(ctx, oracle):
+    """The calls neither allocate nor synchronise, so a caller may capture them. Replays are
+    interleaved with eager work and every replay is checked against the eager result."""
+    from conftest import workload_with_margin
+    w, grads, ref = workload_with_margin("resnet18", P=700_001, N=8)
+    dev = [x.cuda() for x in grads]
+    out = torch.empty(w.P, device="cuda"); mask = torch.empty(w.N, dtype=torch.uint8, device="cuda")
+    dist = torch.empty(w.N, device="cuda"); count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    accum = torch.empty(w.P, device="cuda"); scount = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sdist = torch.empty(w.N, device="cuda"); smask = torch.empty(w.N, dtype=torch.uint8, device="cuda")
+
+    def work():
+        gaf.gaf_aggregate(ctx, dev, w.tau, out, mask, dist, count)
+        scount.fill_(0)
+        for i, g in enumerate(dev):
+            gaf.gaf_step(ctx, accum, scount, g, w.tau, sdist[i:i + 1], smask[i:i + 1])
+
+    work()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (out, mask, dist, count, accum, smask, sdist, scount)]
+    check_against_oracle((out, mask, dist, count), ref, "f32")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for rep in range(4):
+        for t in (out, dist, accum, sdist):
+            t.fill_(float(rep))                      # eager work between replays
+        mask.zero_(); smask.zero_(); count.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((out, mask, dist, count, accum, smask, sdist, scount), eager):
+            assert torch.equal(got, want), rep
