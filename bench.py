@@ -196,10 +196,15 @@ def main():
             else:
                 r["alu_frac"] = frac2
         else:
-            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups
+            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups. binary32 rows in
+            # three or four groups are multiplied through a three-way bfloat16 split (six bf16 MFMAs
+            # per product), everything else in its own type.
             ng = (N + 15) // 16
             flops = 2.0 * (ng * (ng + 1) // 2) * 256 * P
             peak_tf = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
+            if w.dtype == "f32" and ng >= 3:
+                flops *= 6
+                peak_tf = PEAK_MFMA_BF16_TFLOPS
             mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / peak_tf
             if mfma_frac > r["frac"]:
                 r = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": peak_tf,

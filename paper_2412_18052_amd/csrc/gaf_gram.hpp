@@ -107,7 +107,38 @@ __device__ __forceinline__ void gram_mma(const u32x4_t &x, const u32x4_t &y, flo
                                                       __builtin_bit_cast(bf16x8_t, y), acc, 0, 0, 0);
 }
 
-template <typename T, int NG, int kMode>
+// Splits 8 binary32 values into three bfloat16 vectors with x = hi + mid + lo
+// (each step rounds to nearest even and subtracts exactly, so the residuals have
+// no preferred sign). hi*hi + hi*mid + mid*hi + mid*mid + hi*lo + lo*hi then
+// reproduces x*y to about 2^-23 relative -- binary32 product accuracy -- with six
+// bfloat16 MFMAs that together take 3/8 of the time of the binary32 MFMAs they
+// replace.
+__device__ __forceinline__ void split3(const u32x4_t &w0, const u32x4_t &w1, bf16x8_t &hi, bf16x8_t &mid,
+                                       bf16x8_t &lo)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float x = __uint_as_float(e < 4 ? w0[e & 3] : w1[e & 3]);
+        const __bf16 h = (__bf16)x;
+        const float r1 = x - (float)h;
+        const __bf16 m = (__bf16)r1;
+        const float r2 = r1 - (float)m;
+        hi[e] = h;
+        mid[e] = m;
+        lo[e] = (__bf16)r2;
+    }
+}
+
+__device__ __forceinline__ void mma_bf16(const bf16x8_t &x, const bf16x8_t &y, floatx4 &acc)
+{
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc, 0, 0, 0);
+}
+
+// kSplit (binary32 rows only): multiply through the three-way bfloat16 split
+// instead of binary32 MFMAs. Used where the binary32 matrix rate would bind
+// (three or four row groups); with one or two groups the kernel is memory bound
+// either way and the split would only add vector-ALU work.
+template <typename T, int NG, int kMode, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
 __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
 {
     typedef TileList<NG, kMode> Tiles;
@@ -190,6 +221,31 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
                 *reinterpret_cast<u32x4_t *>(&stage[buf * kStageWords + lword[j] + m * 64]) = pre[j][m];
     };
     auto compute = [&](int buf) {
+        if (kSplit) {
+            static_assert(M % 2 == 0, "the split path consumes 32 columns per MFMA");
+#pragma unroll
+            for (int c = 0; c < M / 2; ++c) {
+                bf16x8_t hi[NG], mid[NG], lo[NG];
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const uint32_t *src = &stage[buf * kStageWords + (g * 16 + l16) * kRowWords +
+                                                 wave * 16 * M + c * 32 + sub * 8];
+                    split3(*reinterpret_cast<const u32x4_t *>(src), *reinterpret_cast<const u32x4_t *>(src + 4),
+                           hi[g], mid[g], lo[g]);
+                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int ga = Tiles::ga(t), gb = Tiles::gb(t);
+                    mma_bf16(hi[ga], hi[gb], acc[t]);
+                    mma_bf16(hi[ga], mid[gb], acc[t]);
+                    mma_bf16(mid[ga], hi[gb], acc[t]);
+                    mma_bf16(mid[ga], mid[gb], acc[t]);
+                    mma_bf16(hi[ga], lo[gb], acc[t]);
+                    mma_bf16(lo[ga], hi[gb], acc[t]);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int c = 0; c < M; ++c) {
             u32x4_t x[NG];

@@ -243,6 +243,28 @@ def test_zero_vector_and_nan(ctx, oracle):
     assert torch.equal(accum.cpu(), x) and int(count.item()) == 1 and m1.item() == 0
 
 
+@pytest.mark.parametrize("N,dtype", [(20, "f32"), (40, "f32"), (40, "bf16")])
+def test_nan_and_inf_in_matrix_core_batches(ctx, oracle, N, dtype):
+    # a NaN or Inf in one gradient must poison that gradient's distance only
+    name = "large" if dtype == "bf16" else "resnet18"
+    w, grads, ref = workload_with_margin(name, P=120_011, N=N, seed=N)
+    bad = [g.clone() for g in grads]
+    bad[3][77] = float("nan")
+    bad[N - 2][5] = float("inf")
+    clean = [g for i, g in enumerate(grads) if i not in (3, N - 2)]
+    ref2 = oracle.aggregate(oracle_arrays(clean), np.float32(w.tau))
+    if not np.all(np.abs(ref2[2][1:] - np.float32(w.tau)) >= MARGIN):
+        pytest.skip("margin lost after removing two gradients")
+    out, mask, dist, count = gaf.gaf_aggregate(ctx, [g.cuda() for g in bad], w.tau)
+    torch.cuda.synchronize()
+    m = mask.cpu().numpy(); d = dist.cpu().numpy()
+    assert m[3] == 0 and m[N - 2] == 0 and math.isnan(d[3]) and math.isnan(d[N - 2])
+    keep = [i for i in range(N) if i not in (3, N - 2)]
+    assert m[keep].tolist() == ref2[1].tolist() and int(count.item()) == ref2[3]
+    assert np.max(np.abs(d[keep].astype(np.float64) - ref2[2])) <= DIST_ATOL
+    assert rel_l2(out.cpu().numpy(), ref2[0]) <= OUT_RTOL[dtype]
+
+
 def test_order_dependence(ctx, oracle):
     w, grads = wl.generate("large", 4, P=300_017)
     order = list(range(w.N))
