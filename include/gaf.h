@@ -246,8 +246,10 @@ gaf_status gaf_aggregate_sgd(gaf_ctx *ctx, const void *const *grads, int N, size
  *   accept_mask     DEVICE, B*N bytes, row b = bucket b.
  *   cos_dist        DEVICE, B*N binary32, row b = bucket b.
  *   count           DEVICE, B int32.
- * Each bucket is one batch call under the context's schedule, enqueued in
- * bucket order on `stream`.
+ * For N <= 8 and B <= 256 (unless the sequential schedule is forced) all
+ * buckets are served by three launches: a segmented Gram pass, one filter
+ * workgroup per bucket, a segmented mean. Otherwise each bucket is one batch
+ * call under the context's schedule, enqueued in bucket order on `stream`.
  */
 gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
                                   gaf_dtype dt, float tau, int B, const size_t *bucket_offsets,

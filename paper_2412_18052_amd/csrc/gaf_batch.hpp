@@ -127,17 +127,25 @@ struct SmallGramArgs {
     double *partials;     // [pairs][kMaxBlocks]
 };
 
+__host__ __device__ constexpr int small_gram_unroll(int n) { return n <= 4 ? 4 : 2; }   // 16-byte units per thread per tile
+__host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlock) * small_gram_unroll(n) * 4; }
+
+// Inner products of all pairs of N rows over the element range [lo, hi), for the
+// tiles first, first + stride, ... of that range; the workgroup's sums end up in
+// out[pair] for pair = 0 .. N(N+1)/2 - 1 (row-major upper triangle), written by
+// the first N(N+1)/2 threads. lo must be a multiple of 8 elements.
 template <typename T, int N, bool kStream>
-__global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
+__device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
+                                                 size_t first, size_t stride, double *out, size_t out_stride)
 {
     constexpr int NP = N * (N + 1) / 2;
-    constexpr int U = N <= 4 ? 4 : 2;                       // 16-byte units per thread per tile
-    constexpr size_t tile = size_t(kBlock) * U * 4;
+    constexpr int U = small_gram_unroll(N);
+    constexpr size_t tile = small_gram_tile(N);
     __shared__ double lds[NP][kWaves];
 
     const T *row[N];
 #pragma unroll
-    for (int i = 0; i < N; ++i) row[i] = static_cast<const T *>(a.rows[i]);
+    for (int i = 0; i < N; ++i) row[i] = static_cast<const T *>(rows[i]);
     double acc[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
@@ -153,11 +161,10 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
             for (int j = i; j < N; ++j, ++k) acc[k] = __builtin_fma(d[i], d[j], acc[k]);
     };
 
-    const size_t P = a.P;
-    const size_t ntiles = (P + tile - 1) / tile;
-    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const size_t base = t * tile + size_t(threadIdx.x) * 4;
-        if ((t + 1) * tile <= P) {
+    const size_t ntiles = (hi - lo + tile - 1) / tile;
+    for (size_t t = first; t < ntiles; t += stride) {
+        const size_t base = lo + t * tile + size_t(threadIdx.x) * 4;
+        if (lo + (t + 1) * tile <= hi) {
             float4 v[U][N];
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -183,7 +190,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
             for (int u = 0; u < U; ++u)
                 for (int e = 0; e < 4; ++e) {
                     const size_t idx = base + size_t(u) * kBlock * 4 + e;
-                    if (idx >= P) continue;
+                    if (idx >= hi) continue;
                     float x[N];
 #pragma unroll
                     for (int i = 0; i < N; ++i) x[i] = load1(row[i], idx);
@@ -203,8 +210,15 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
         double v = lds[threadIdx.x][0];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) v += lds[threadIdx.x][w];
-        a.partials[size_t(threadIdx.x) * kMaxBlocks + blockIdx.x] = v;
+        out[size_t(threadIdx.x) * out_stride] = v;
     }
+}
+
+template <typename T, int N, bool kStream>
+__global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
+{
+    // partials laid out [pair][kMaxBlocks]
+    gram_small_range<T, N, kStream>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x, kMaxBlocks);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner
@@ -259,31 +273,22 @@ __device__ __forceinline__ void sgd_element(float g, float &theta, float &v, flo
 // of parameters and momentum, no separate optimizer pass); with c == 1 there is
 // no consensus and parameters and optimizer state are left untouched
 // (Algorithm 1's skip).
+// Mean of the accepted gradients (and, with kSgd, the fused optimizer step) over
+// the element range [lo, hi), tiles first, first + stride, ... of that range.
+// table/list live in LDS: pointers of all gradients, indices of the accepted ones.
 template <typename T, bool kStream, bool kSgd>
-__global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
+__device__ __forceinline__ void mean_range(const MeanArgs &a, const void *const *table, const int32_t *list,
+                                           int c, size_t lo, size_t hi, size_t first, size_t stride)
 {
-    __shared__ const void *table[kBatchMaxN];
-    __shared__ int32_t list[kBatchMaxN];
-    const int c = a.st->count;
-    if (threadIdx.x < kBatchMaxN) {
-        const void *p = nullptr;
-#pragma unroll
-        for (int k = 0; k < kBatchMaxN; ++k)
-            if (int(threadIdx.x) == k) p = a.rows[k];
-        table[threadIdx.x] = p;
-        list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;
-    }
-    __syncthreads();
     const float inv_c = 1.0f / (float)c;
-    const size_t P = a.P;
-    const size_t ntiles = (P + kTile - 1) / kTile;
+    const size_t ntiles = (hi - lo + kTile - 1) / kTile;
     float *out = a.out;
     const bool step = kSgd && c > 1;
     if (kSgd && !step && !out) return;      // skipped step, nothing else asked for
 
-    for (size_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const size_t base = t * kTile + size_t(threadIdx.x) * 4;
-        if ((t + 1) * kTile <= P) {
+    for (size_t t = first; t < ntiles; t += stride) {
+        const size_t base = lo + t * kTile + size_t(threadIdx.x) * 4;
+        if (lo + (t + 1) * kTile <= hi) {
             float4 sum[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) sum[u] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -344,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
             for (int u = 0; u < kUnroll; ++u)
                 for (int e = 0; e < 4; ++e) {
                     const size_t idx = base + size_t(u) * kBlock * 4 + e;
-                    if (idx >= P) continue;
+                    if (idx >= hi) continue;
                     float sum = 0.f;
                     for (int k = 0; k < c; ++k) sum += load1(static_cast<const T *>(table[list[k]]), idx);
                     const float o = sum * inv_c;
@@ -353,6 +358,129 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
                 }
         }
     }
+}
+
+template <typename T, bool kStream, bool kSgd>
+__global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
+{
+    __shared__ const void *table[kBatchMaxN];
+    __shared__ int32_t list[kBatchMaxN];
+    const int c = a.st->count;
+    if (threadIdx.x < kBatchMaxN) {
+        table[threadIdx.x] = a.rows[threadIdx.x];
+        list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;
+    }
+    __syncthreads();
+    mean_range<T, kStream, kSgd>(a, table, list, c, 0, a.P, blockIdx.x, gridDim.x);
+}
+
+// ---- bucketed filtering in three launches (small batches) -------------------
+// Bucket b covers elements [off[b], off[b+1]) and is served by workgroups
+// [blk[b], blk[b+1]) of the Gram and of the mean launch; both tables travel in
+// the kernel-argument segment.
+constexpr int kSegMaxBuckets = 256;
+constexpr int kSegMaxBlocks = 32768;     // workgroups over all buckets (size of the partial-sum table)
+
+struct SegTable {
+    unsigned long long off[kSegMaxBuckets + 1];
+    int32_t blk[kSegMaxBuckets + 1];
+    int B;
+};
+
+struct SegWs {                           // per-bucket outcome of the filter, read by the mean launch
+    int32_t list[kSegMaxBuckets][kSmallMaxN];
+    int32_t count[kSegMaxBuckets];
+};
+
+__device__ __forceinline__ int seg_bucket_of(const SegTable &tab, int wg)
+{
+    int lo = 0, hi = tab.B - 1;          // largest b with blk[b] <= wg
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (tab.blk[mid] <= wg) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+struct SegGramArgs {
+    const void *rows[kSmallMaxN];
+    SegTable tab;
+    double *partials;                    // [workgroup][kSmallMaxPairs]
+};
+
+template <typename T, int N, bool kStream>
+__global__ __launch_bounds__(kBlock) void gram_seg_kernel(SegGramArgs a)
+{
+    const int b = seg_bucket_of(a.tab, blockIdx.x);
+    const int first = a.tab.blk[b], nblk = a.tab.blk[b + 1] - first;
+    gram_small_range<T, N, kStream>(a.rows, a.tab.off[b], a.tab.off[b + 1], blockIdx.x - first, nblk,
+                                    a.partials + size_t(blockIdx.x) * kSmallMaxPairs, 1);
+}
+
+// One workgroup per bucket: ordered sum of the bucket's partial inner products
+// (thread = (pair, slice of the bucket's workgroups); slices added in order),
+// then Algorithm 1 replayed on the bucket's Gram matrix by the first wavefront.
+__global__ __launch_bounds__(kBlock) void seg_filter_kernel(const double *partials, SegTable tab, int N, float tau,
+                                                            uint8_t *mask, float *cos_dist, int32_t *count,
+                                                            SegWs *ws)
+{
+    __shared__ double red[kWaves][64];
+    __shared__ double g[kSmallMaxN * kSmallMaxN];
+    const int b = blockIdx.x;
+    const int first = tab.blk[b], last = tab.blk[b + 1];
+    const int np = N * (N + 1) / 2;
+    const int pair = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    double s = 0.0;
+    if (pair < np)
+        for (int w = first + slice; w < last; w += kWaves) s += partials[size_t(w) * kSmallMaxPairs + pair];
+    red[slice][pair] = s;
+    __syncthreads();
+    if (int(threadIdx.x) < np) {
+        double v = red[0][pair];
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) v += red[k][pair];
+        int i = 0, left = pair;           // pair index -> (i, j), j >= i, row-major upper triangle
+        while (left >= N - i) {
+            left -= N - i;
+            ++i;
+        }
+        const int j = i + left;
+        g[i * N + j] = v;
+        g[j * N + i] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const int c = run_filter(g, N, 0, tau, mask + size_t(b) * N, cos_dist + size_t(b) * N, ws->list[b]);
+        if (threadIdx.x == 0) {
+            count[b] = c;
+            ws->count[b] = c;
+        }
+    }
+}
+
+struct SegMeanArgs {
+    MeanArgs m;                          // rows, out (P, accepted_list, st unused)
+    SegTable tab;
+    const SegWs *ws;
+};
+
+static_assert(sizeof(SegMeanArgs) <= 4096 && sizeof(SegGramArgs) <= 4096, "kernel arguments must fit 4 KB");
+
+template <typename T, bool kStream>
+__global__ __launch_bounds__(kBlock) void mean_seg_kernel(SegMeanArgs a)
+{
+    __shared__ const void *table[kBatchMaxN];
+    __shared__ int32_t list[kBatchMaxN];
+    const int b = seg_bucket_of(a.tab, blockIdx.x);
+    const int first = a.tab.blk[b], nblk = a.tab.blk[b + 1] - first;
+    const int c = a.ws->count[b];
+    if (threadIdx.x < kBatchMaxN) {
+        table[threadIdx.x] = a.m.rows[threadIdx.x];
+        list[threadIdx.x] = int(threadIdx.x) < c ? a.ws->list[b][threadIdx.x] : 0;
+    }
+    __syncthreads();
+    mean_range<T, kStream, false>(a.m, table, list, c, a.tab.off[b], a.tab.off[b + 1], blockIdx.x - first, nblk);
 }
 
 }  // namespace gaf

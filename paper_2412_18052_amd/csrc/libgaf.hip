@@ -24,6 +24,7 @@ struct gaf_ctx {
     double *gram_full;   // device, [max_N][max_N]
     int32_t *accepted;   // device, [max_N] indices of accepted gradients (Gram-first schedule)
     SeedWs *seed_ws;     // device, per-seed filter runs (order-indifferent variant)
+    SegWs *seg_ws;       // device, per-bucket filter outcomes (bucketed filtering)
     gaf_schedule schedule;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
@@ -410,6 +411,75 @@ gaf_status gram_first_dispatch(gaf_ctx *ctx, const void *const *grads, int N, si
               : aggregate_gram_impl<bf16_t, false>(ctx, grads, N, P, tau, gram, out, mask, cos_dist, count, s);
 }
 
+static_assert(size_t(kSegMaxBlocks) * kSmallMaxPairs <= size_t(kGramBlocks) * kGramMaxTiles * kGramTile,
+              "the bucketed partial-sum table reuses the Gram workspace");
+
+template <typename T, bool kStream, int N>
+gaf_status gram_seg_launch(const SegGramArgs &g, int nblocks, hipStream_t s)
+{
+    gram_seg_kernel<T, N, kStream><<<nblocks, kBlock, 0, s>>>(g);
+    return launched();
+}
+
+// Bucketed filtering for small batches in three launches whatever the number of
+// buckets: segmented Gram, one filter workgroup per bucket, segmented mean.
+template <typename T, bool kStream>
+gaf_status bucketed_seg_impl(gaf_ctx *ctx, const void *const *grads, int N, float tau, int B,
+                             const size_t *off, float *out, uint8_t *mask, float *cos_dist,
+                             int32_t *count, hipStream_t s)
+{
+    SegGramArgs g{};
+    for (int i = 0; i < kSmallMaxN; ++i) g.rows[i] = grads[i < N ? i : 0];
+    g.tab.B = B;
+    g.partials = ctx->gram_ws;
+    // workgroups per bucket: one per tile of the Gram kernel, capped so that all buckets together
+    // stay within the partial-sum table
+    const size_t tile = small_gram_tile(N);
+    const int cap = kSegMaxBlocks / B < 256 ? kSegMaxBlocks / B : 256;
+    int total = 0;
+    for (int b = 0; b < B; ++b) {
+        const size_t ntiles = (off[b + 1] - off[b] + tile - 1) / tile;
+        g.tab.off[b] = off[b];
+        g.tab.blk[b] = total;
+        total += ntiles < size_t(cap) ? static_cast<int>(ntiles) : cap;
+    }
+    g.tab.off[B] = off[B];
+    g.tab.blk[B] = total;
+    gaf_status rc = GAF_OK;
+    {
+        Timed t(ctx, s, GAF_K_GRAM);
+        switch (N) {
+        case 1: rc = gram_seg_launch<T, kStream, 1>(g, total, s); break;
+        case 2: rc = gram_seg_launch<T, kStream, 2>(g, total, s); break;
+        case 3: rc = gram_seg_launch<T, kStream, 3>(g, total, s); break;
+        case 4: rc = gram_seg_launch<T, kStream, 4>(g, total, s); break;
+        case 5: rc = gram_seg_launch<T, kStream, 5>(g, total, s); break;
+        case 6: rc = gram_seg_launch<T, kStream, 6>(g, total, s); break;
+        case 7: rc = gram_seg_launch<T, kStream, 7>(g, total, s); break;
+        default: rc = gram_seg_launch<T, kStream, 8>(g, total, s); break;
+        }
+    }
+    if (rc != GAF_OK) return rc;
+    {
+        Timed t(ctx, s, GAF_K_FILTER);
+        seg_filter_kernel<<<B, kBlock, 0, s>>>(ctx->gram_ws, g.tab, N, tau, mask, cos_dist, count,
+                                               ctx->seg_ws);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    SegMeanArgs m{};
+    for (int i = 0; i < kBatchMaxN; ++i) m.m.rows[i] = grads[i < N ? i : 0];
+    m.m.N = N;
+    m.m.out = out;
+    m.m.P = off[B];
+    m.tab = g.tab;
+    m.ws = ctx->seg_ws;
+    {
+        Timed t(ctx, s, GAF_K_MEAN);
+        mean_seg_kernel<T, kStream><<<total, kBlock, 0, s>>>(m);
+    }
+    return launched();
+}
+
 // Schedule selection of the plain batch call (arguments already validated).
 gaf_status aggregate_dispatch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,
                               float tau, float *out, uint8_t *accept_mask, float *cos_dist,
@@ -495,7 +565,8 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
               hipMalloc(reinterpret_cast<void **>(&ctx->gram_full), gram_full_bytes) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->accepted),
                         sizeof(int32_t) * size_t(max_N < kBatchMaxN ? kBatchMaxN : max_N)) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void **>(&ctx->seed_ws), sizeof(SeedWs)) == hipSuccess;
+              hipMalloc(reinterpret_cast<void **>(&ctx->seed_ws), sizeof(SeedWs)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->seg_ws), sizeof(SegWs)) == hipSuccess;
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -521,6 +592,7 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->gram_full) (void)hipFree(ctx->gram_full);
     if (ctx->accepted) (void)hipFree(ctx->accepted);
     if (ctx->seed_ws) (void)hipFree(ctx->seed_ws);
+    if (ctx->seg_ws) (void)hipFree(ctx->seg_ws);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;
@@ -656,6 +728,15 @@ gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N,
         if (bucket_offsets[b] % 8 != 0) return GAF_EALIGN;   // keeps every slice 16-byte aligned
     }
     if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (N <= kSmallMaxN && B <= kSegMaxBuckets && ctx->schedule != GAF_SCHEDULE_SEQUENTIAL) {
+        const bool big = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
+        if (dt == GAF_F32)
+            return big ? bucketed_seg_impl<float, true>(ctx, grads, N, tau, B, bucket_offsets, out, accept_mask, cos_dist, count, st)
+                       : bucketed_seg_impl<float, false>(ctx, grads, N, tau, B, bucket_offsets, out, accept_mask, cos_dist, count, st);
+        return big ? bucketed_seg_impl<bf16_t, true>(ctx, grads, N, tau, B, bucket_offsets, out, accept_mask, cos_dist, count, st)
+                   : bucketed_seg_impl<bf16_t, false>(ctx, grads, N, tau, B, bucket_offsets, out, accept_mask, cos_dist, count, st);
+    }
     const size_t es = dt == GAF_F32 ? 4 : 2;
     std::vector<const void *> slice(static_cast<size_t>(N));
     for (int b = 0; b < B; ++b) {

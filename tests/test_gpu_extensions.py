@@ -144,6 +144,34 @@ def test_bucketed_parity(ctx, oracle, name, P, N, dtype):
     assert len(set(map(tuple, ref[1].tolist()))) >= 1
 
 
+@pytest.mark.parametrize("N,dtype", [(2, "f32"), (8, "f32"), (5, "bf16")])
+def test_bucketed_many_layers(ctx, oracle, N, dtype):
+    # per-layer buckets of a convolutional network: many small tensors, a few large ones
+    rng = np.random.default_rng(7)
+    sizes = [8, 64, 64, 1728, 64, 36_864, 128, 73_728, 128, 147_456, 256, 8, 16, 294_912, 512, 5_128] * 4
+    sizes = [int(x) for x in sizes[:62]]
+    offs = [0] + np.cumsum(sizes).tolist()
+    P = offs[-1]
+    name = "large" if dtype == "bf16" else "resnet18"
+    for seed in range(24):
+        w, grads = wl.generate(name, seed, P=P, N=N)
+        a = oracle_arrays(grads)
+        ref = oracle.bucketed(a, np.float32(w.tau), offs)
+        if np.all(np.abs(ref[2][:, 1:] - float(np.float32(w.tau))) >= MARGIN):
+            break
+    else:
+        pytest.skip("no seed keeps the margin in all 62 buckets")
+    out, mask, dist, count = gaf.gaf_aggregate_bucketed(ctx, [x.cuda() for x in grads], w.tau, offs)
+    torch.cuda.synchronize()
+    assert mask.cpu().numpy().tolist() == ref[1].tolist()
+    assert count.cpu().numpy().tolist() == ref[3].tolist()
+    assert np.max(np.abs(dist.cpu().numpy().astype(np.float64) - ref[2])) <= DIST_ATOL
+    o = out.cpu().numpy()
+    for b in range(len(sizes)):
+        assert rel_l2(o[offs[b]:offs[b + 1]], ref[0][offs[b]:offs[b + 1]]) <= OUT_RTOL[dtype], b
+    assert len({tuple(r) for r in ref[1].tolist()}) > 1     # buckets really decide differently
+
+
 def test_extension_argument_errors(ctx):
     lib = gaf.load()
     P = 4096
