@@ -226,17 +226,15 @@ int oracle_gaf_best_seed(const void *const *grads, int N, size_t P, int dtype, d
     double *tmp = (double *)malloc(sizeof(double) * P);
     uint8_t *m = (uint8_t *)malloc((size_t)N);
     double *d = (double *)malloc(sizeof(double) * (size_t)N);
-    if (!ring || !tmp || !m || !d)
-        return 2;
-    int best = -1;
+    int best = -1, rc = (!ring || !tmp || !m || !d) ? 2 : 0;
     int32_t best_c = 0;
-    for (int s = 0; s < N; ++s) {
+    for (int s = 0; s < N && !rc; ++s) {
         for (int k = 0; k < N; ++k)
             ring[k] = grads[(s + k) % N];
         int32_t c = 0;
-        int rc = oracle_gaf_aggregate(ring, N, P, dtype, tau, tmp, m, d, &c);
+        rc = oracle_gaf_aggregate(ring, N, P, dtype, tau, tmp, m, d, &c);
         if (rc)
-            return rc;
+            break;
         if (counts_all)
             counts_all[s] = c;
         if (c > best_c) {
@@ -255,7 +253,7 @@ int oracle_gaf_best_seed(const void *const *grads, int N, size_t P, int dtype, d
     free(tmp);
     free(m);
     free(d);
-    return 0;
+    return rc;
 }
 
 /*
@@ -299,16 +297,17 @@ int oracle_gaf_bucketed(const void *const *grads, int N, size_t P, int dtype, do
     const void **sl = (const void **)malloc(sizeof(void *) * (size_t)N);
     if (!sl)
         return 2;
-    for (int b = 0; b < B; ++b) {
-        if (off[b + 1] <= off[b])
-            return 1;
+    int rc = 0;
+    for (int b = 0; b < B && !rc; ++b) {
+        if (off[b + 1] <= off[b]) {
+            rc = 1;
+            break;
+        }
         for (int i = 0; i < N; ++i)
             sl[i] = (const char *)grads[i] + off[b] * es;
-        int rc = oracle_gaf_aggregate(sl, N, off[b + 1] - off[b], dtype, tau, out + off[b],
-                                      mask + (size_t)b * N, dist + (size_t)b * N, &count[b]);
-        if (rc)
-            return rc;
+        rc = oracle_gaf_aggregate(sl, N, off[b + 1] - off[b], dtype, tau, out + off[b],
+                                  mask + (size_t)b * N, dist + (size_t)b * N, &count[b]);
     }
     free(sl);
-    return 0;
+    return rc;
 }
