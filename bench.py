@@ -104,6 +104,11 @@ def main():
         schedule_used = "sequential"
     else:
         schedule_used = "gram_first"
+    # long vectors on the matrix-core path: the Gram pass also writes the mean of a guessed accept set
+    fused = (schedule_used == "gram_first" and args.schedule == "auto" and N > 8 and P >= (1 << 26)
+             and w.mode != "pairwise")
+    if fused:
+        schedule_used = "gram_first_fused_mean"
 
     out = torch.empty(P, dtype=torch.float32, device="cuda")
     mask = torch.empty(N, dtype=torch.uint8, device="cuda")
@@ -184,7 +189,7 @@ def main():
         # one launch reads every gradient once
         dur = per_kernel["gram"]
         avg_ms = sum(dur) / len(dur)
-        alg_bytes = float(N * s * P)
+        alg_bytes = float(N * s * P) + (4.0 * P if fused else 0.0)   # fused: the result is written too
         r = hbm_roof(alg_bytes, avg_ms)
         if N <= 8:
             # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
@@ -212,7 +217,7 @@ def main():
             else:
                 r["mfma_frac"] = mfma_frac
         roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
-    if "mean" in per_kernel:
+    if "mean" in per_kernel and not fused:     # fused: the stand-alone mean only runs after a wrong guess
         dur = per_kernel["mean"]
         avg_ms = sum(dur) / len(dur)
         alg_bytes = float(c_h * s * P + 4 * P)      # accepted gradients read once, result written once
@@ -250,21 +255,32 @@ def main():
         if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
             roof["traffic"] = ent["hbm_bytes_per_launch"]
 
-    # ---- the other schedule of the batch call, for comparison (fewer steps) ----
+    # ---- the other schedules of the batch call, for comparison (fewer steps) ----
     other = None
     if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64:
-        gaf.gaf_set_schedule(ctx, "sequential")
-        state["schedule"] = "sequential"
-        k = max(3, args.steps // 4)
-        step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(k):
+        other = []
+        for sched in (["gram"] if fused else []) + ["sequential"]:
+            gaf.gaf_set_schedule(ctx, sched)
+            state["schedule"] = sched
+            k = max(3, args.steps // 4)
             step()
-        torch.cuda.synchronize()
-        ms_seq = 1e3 * (time.perf_counter() - t0) / k
-        other = {"schedule": "sequential", "steps": k, "ms_per_step": ms_seq,
-                 "value": step_bytes / (ms_seq * 1e-3) / 1e9}
+            torch.cuda.synchronize()
+            gaf.gaf_profile_begin(ctx, 65536)
+            t0 = time.perf_counter()
+            for _ in range(k):
+                step()
+            torch.cuda.synchronize()
+            ms_o = 1e3 * (time.perf_counter() - t0) / k
+            kt = {}
+            for name, ms in gaf.gaf_profile_end(ctx, 65536):
+                kt.setdefault(name, []).append(ms)
+            entry = {"schedule": "gram_two_pass" if sched == "gram" else sched, "steps": k,
+                     "ms_per_step": ms_o, "value": step_bytes / (ms_o * 1e-3) / 1e9,
+                     "kernel_ms": {n: sum(v) / len(v) for n, v in kt.items()}}
+            if sched == "gram" and "gram" in kt:
+                g_ms = sum(kt["gram"]) / len(kt["gram"])
+                entry["gram_kernel_hbm_frac"] = N * s * P / (g_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS
+            other.append(entry)
         gaf.gaf_set_schedule(ctx, args.schedule)
         state["schedule"] = args.schedule
 
@@ -329,7 +345,7 @@ def main():
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "other_schedule": other,
+        "other_schedules": other,
         "kernel_ms": {k: sum(v) / len(v) for k, v in per_kernel.items()},
         "accept_mask": mask_h,
         "cos_dist": [round(x, 6) for x in dist_h],

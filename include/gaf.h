@@ -132,6 +132,12 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *               Algorithm 1 on the device, then Eq. 5 as one masked mean over
  *               the accepted gradients (c reads, one write). 2 <= N <= 64.
  *   AUTO        GRAM when 2 <= N <= 64, otherwise SEQUENTIAL. The default.
+ *               For long vectors (P >= 2^26) and N > 8 AUTO additionally guesses
+ *               the accept set from the first 2^22 elements and lets the Gram pass
+ *               write the mean of that guess while it has the data staged on chip;
+ *               once the full inner products are known the guess is checked on the
+ *               device, and only a wrong guess costs the separate mean pass. The
+ *               result is the same either way, bit for bit.
  * Explicit GRAM with N outside its range returns GAF_EUNSUPPORTED.
  */
 typedef enum {
@@ -276,7 +282,8 @@ typedef enum {
     GAF_K_DISTANCE = 6,      /* Gram matrix -> distance matrix */
     GAF_K_DECIDE = 7,        /* ordered sum of the partial sums, distance, accept/reject decision */
     GAF_K_FILTER = 8,        /* Gram-first schedule: Algorithm 1 replayed on the Gram matrix */
-    GAF_K_MEAN = 9           /* Gram-first schedule: mean of the accepted gradients (Eq. 5) */
+    GAF_K_MEAN = 9,          /* Gram-first schedule: mean of the accepted gradients (Eq. 5) */
+    GAF_K_GRAM_SAMPLE = 10   /* inner products over a prefix of the vectors, to guess the accept set */
 } gaf_kernel_id;
 
 typedef struct {

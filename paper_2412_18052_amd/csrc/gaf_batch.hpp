@@ -13,6 +13,7 @@
 // rounding; the distances here come from exact-product binary64 sums.
 #pragma once
 #include "gaf_device.hpp"
+#include "gaf_gram.hpp"
 #include "gaf_pass.hpp"
 
 namespace gaf {
@@ -252,6 +253,8 @@ struct MeanArgs {
     const State *st;                // st->count = c
     float *out;                     // may be NULL in the fused-optimizer form
     size_t P;
+    const Prediction *pred;         // non-NULL: `out` already holds the mean of this predicted accept set;
+                                    // the launch has work to do only if the prediction was wrong
     // fused GAF-SGD step (kSgd): parameters and momentum buffer, in place
     float *theta, *vel;
     float lr, mu, wd;
@@ -366,6 +369,11 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
     __shared__ const void *table[kBatchMaxN];
     __shared__ int32_t list[kBatchMaxN];
     const int c = a.st->count;
+    if (a.pred) {
+        bool same = a.pred->count == c;
+        for (int k = 0; same && k < c; ++k) same = a.pred->list[k] == a.accepted_list[k];
+        if (same) return;           // the fused pass already wrote exactly this mean
+    }
     if (threadIdx.x < kBatchMaxN) {
         table[threadIdx.x] = a.rows[threadIdx.x];
         list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;

@@ -70,11 +70,21 @@ struct TileList {
 // 3-4 KB of loads in flight per wavefront whatever the row count.
 __host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 8 : ng == 2 ? 4 : 2; }
 
+// An accept set guessed before the full inner products are known (from a prefix
+// of the vectors): which gradients Algorithm 1 will probably accept, in visiting order.
+struct Prediction {
+    int32_t count;
+    int32_t list[kGramRows];
+};
+
 struct GramArgs {
     const void *rows[kGramRows];  // DEVICE pointers, group g = rows[16 g .. 16 g + 15]; never NULL: rows past
                                   // the last gradient alias a real one and their tile entries are dropped
     size_t P;
     double *ws;                   // [kGramBlocks][kGramMaxTiles][kGramTile] per-workgroup tiles
+    // kMean only: the mean of the predicted accept set is formed from the staged data and written here
+    const Prediction *pred;
+    float *out;
 };
 
 // 16 bytes of a row starting at element p, element-wise and zero past the end.
@@ -134,12 +144,19 @@ __device__ __forceinline__ void mma_bf16(const bf16x8_t &x, const bf16x8_t &y, f
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc, 0, 0, 0);
 }
 
+// kMean: while a stage sits in LDS, the mean (Eq. 5) of the gradients a
+// Prediction names is formed from it and written to a.out -- same summation
+// order and arithmetic as the stand-alone mean kernel, so the values are
+// bit-identical to what that kernel would write for the same accept set. If the
+// prediction turns out right (checked on the device once the full inner
+// products are known) the accepted gradients are never read a second time.
+//
 // kSplit (binary32 rows only): multiply through the three-way bfloat16 split
 // instead of binary32 MFMAs. Used where the binary32 matrix rate would bind
 // (three or four row groups); with one or two groups the kernel is memory bound
 // either way and the split would only add vector-ALU work.
-template <typename T, int NG, int kMode, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
-__global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
+template <typename T, int NG, int kMode, bool kMean = false, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
 {
     typedef TileList<NG, kMode> Tiles;
     constexpr int NT = Tiles::count;
@@ -154,6 +171,7 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
 
     __shared__ __attribute__((aligned(16))) uint32_t stage[2 * kStageWords];
     __shared__ const void *row_table[kGramRows];
+    __shared__ int32_t pred_rows[kGramRows];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, sub = lane >> 4;
@@ -166,6 +184,11 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
         for (int k = 0; k < kRows; ++k)
             if (int(threadIdx.x) == k) p = a.rows[k];
         row_table[threadIdx.x] = p;
+    }
+    int c_pred = 0;
+    if (kMean) {
+        c_pred = a.pred->count;
+        if (int(threadIdx.x) < c_pred) pred_rows[threadIdx.x] = a.pred->list[threadIdx.x];
     }
     __syncthreads();
 
@@ -259,6 +282,41 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
                 for (int t = 0; t < NT; ++t) gram_mma<T>(x[Tiles::ga(t)], x[Tiles::gb(t)], acc[t], e);
         }
     };
+    // Eq. 5 over the predicted accept set for the stage in buffer `buf` (stage index s):
+    // each thread owns 4 consecutive columns, sums the predicted rows in visiting order.
+    auto mean_stage = [&](int buf, size_t s) {
+        constexpr int kQuads = int(kStageElems / 4);
+        const float inv_c = 1.0f / (float)c_pred;
+        const size_t e_base = s * kStageElems;
+        for (int q = threadIdx.x; q < kQuads; q += kBlock) {
+            f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < c_pred; ++k) {
+                const uint32_t *src = &stage[buf * kStageWords + pred_rows[k] * kRowWords];
+                if (sizeof(T) == 4) {
+                    const u32x4_t w = *reinterpret_cast<const u32x4_t *>(src + 4 * q);
+                    sum.x += __uint_as_float(w.x);
+                    sum.y += __uint_as_float(w.y);
+                    sum.z += __uint_as_float(w.z);
+                    sum.w += __uint_as_float(w.w);
+                } else {
+                    const u32x2_t w = *reinterpret_cast<const u32x2_t *>(src + 2 * q);
+                    sum.x += __uint_as_float(w.x << 16);
+                    sum.y += __uint_as_float(w.x & 0xffff0000u);
+                    sum.z += __uint_as_float(w.y << 16);
+                    sum.w += __uint_as_float(w.y & 0xffff0000u);
+                }
+            }
+            const f32x4_t o = {sum.x * inv_c, sum.y * inv_c, sum.z * inv_c, sum.w * inv_c};
+            const size_t idx = e_base + size_t(q) * 4;
+            if (idx + 4 <= P) {
+                __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t *>(a.out + idx));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (idx + e < P) a.out[idx + e] = o[e];
+            }
+        }
+    };
     auto flush = [&]() {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
@@ -278,6 +336,7 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
         while (s + G < nfull) {
             gload(s + G);              // in flight during the MFMAs below
             compute(buf);
+            if (kMean) mean_stage(buf, s);
             if (++since_flush == kGramFlush) {
                 since_flush = 0;
                 flush();
@@ -288,6 +347,7 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
             s += G;
         }
         compute(buf);
+        if (kMean) mean_stage(buf, s);
     }
     // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
     if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
@@ -296,6 +356,7 @@ __global__ __launch_bounds__(kBlock) void gram_kernel(GramArgs a)
         lstore(0);
         __syncthreads();
         compute(0);
+        if (kMean) mean_stage(0, nfull);
     }
     flush();
 

@@ -25,6 +25,7 @@ struct gaf_ctx {
     int32_t *accepted;   // device, [max_N] indices of accepted gradients (Gram-first schedule)
     SeedWs *seed_ws;     // device, per-seed filter runs (order-indifferent variant)
     SegWs *seg_ws;       // device, per-bucket filter outcomes (bucketed filtering)
+    Prediction *pred;    // device, accept set predicted from a prefix (fused mean)
     gaf_schedule schedule;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
@@ -209,9 +210,10 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
 // Enqueues the Gram kernel for up to four 16-row groups (global group indices in
 // `groups`, -1 = absent) and the ordered combine of its per-workgroup tiles into
 // ctx->gram_full (leading dimension N).
+// With `mean_out` the launch also writes the mean of ctx->pred's accept set there (kFull only).
 template <typename T, int NG, int kMode>
 gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, const int (&groups)[4],
-                       hipStream_t s)
+                       hipStream_t s, gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
 {
     typedef TileList<NG, kMode> Tiles;
     GramArgs g{};
@@ -225,9 +227,14 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     }
     g.P = P;
     g.ws = ctx->gram_ws;
+    g.pred = ctx->pred;
+    g.out = mean_out;
     {
-        Timed t(ctx, s, GAF_K_GRAM);
-        gram_kernel<T, NG, kMode><<<kGramBlocks, kBlock, 0, s>>>(g);
+        Timed t(ctx, s, id);
+        if (mean_out && kMode == kFull)
+            gram_kernel<T, NG, kFull, true><<<kGramBlocks, kBlock, 0, s>>>(g);
+        else
+            gram_kernel<T, NG, kMode><<<kGramBlocks, kBlock, 0, s>>>(g);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     f.ws = ctx->gram_ws;
@@ -249,8 +256,10 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
 // Inner products of all pairs into ctx->gram_full. N <= 64: one launch, every
 // gradient read once. Larger N: 64-row panels, then the tiles between 32-row
 // halves of different panels.
+// `mean_out` (N <= 64 only): see gram_launch.
 template <typename T>
-gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s)
+gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
+                          gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
 {
     const int ng = (N + 15) / 16;
     for (int g0 = 0; g0 < ng; g0 += 4) {
@@ -258,10 +267,10 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
         const int groups[4] = {g0, n > 1 ? g0 + 1 : -1, n > 2 ? g0 + 2 : -1, n > 3 ? g0 + 3 : -1};
         gaf_status rc = GAF_OK;
         switch (n) {
-        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s); break;
-        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s); break;
-        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s); break;
-        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s); break;
+        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
+        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
+        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
+        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
         }
         if (rc != GAF_OK) return rc;
     }
@@ -318,6 +327,12 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
     return launched();
 }
 
+// Fused mean (see gram_kernel's kMean): used from this vector length up, with the accept set
+// guessed from this many leading elements. The guess costs N * kSpecSample elements of extra
+// reading (under 1 % at kSpecMinP); a wrong guess costs one stand-alone mean pass.
+constexpr size_t kSpecSample = size_t(1) << 22;
+constexpr size_t kSpecMinP = size_t(1) << 26;
+
 // Variations of the Gram-first batch call.
 struct BatchOptions {
     const double *gram = nullptr;   // caller's matrix of inner products: the Gram pass is skipped
@@ -333,7 +348,23 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                int32_t *count, hipStream_t s)
 {
     const double *gram = opt.gram;
-    if (!gram) {
+    // Long vectors on the matrix-core path: guess the accept set from a prefix, let the Gram pass
+    // write the mean of that guess while the data is staged in LDS, and check the guess afterwards.
+    const bool speculate = !gram && !opt.best_seed && !opt.theta && N > kSmallMaxN && P >= kSpecMinP &&
+                           ctx->schedule == GAF_SCHEDULE_AUTO;
+    if (speculate) {
+        gaf_status rc = gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE);
+        if (rc != GAF_OK) return rc;
+        {
+            Timed t(ctx, s, GAF_K_FILTER);
+            filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, &ctx->seed_ws->mask[0][0],
+                                           &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list);
+        }
+        if (launched() != GAF_OK) return GAF_EHIP;
+        rc = gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out);
+        if (rc != GAF_OK) return rc;
+        gram = ctx->gram_full;
+    } else if (!gram) {
         const gaf_status rc = N <= kSmallMaxN ? gram_small<T, kStream>(ctx, grads, N, P, s)
                                               : gram_all_pairs<T>(ctx, grads, N, P, s);
         if (rc != GAF_OK) return rc;
@@ -362,6 +393,7 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     m.st = ctx->st;
     m.out = out;
     m.P = P;
+    m.pred = speculate ? ctx->pred : nullptr;
     m.theta = opt.theta;
     m.vel = opt.vel;
     m.lr = opt.lr;
@@ -566,7 +598,8 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
               hipMalloc(reinterpret_cast<void **>(&ctx->accepted),
                         sizeof(int32_t) * size_t(max_N < kBatchMaxN ? kBatchMaxN : max_N)) == hipSuccess &&
               hipMalloc(reinterpret_cast<void **>(&ctx->seed_ws), sizeof(SeedWs)) == hipSuccess &&
-              hipMalloc(reinterpret_cast<void **>(&ctx->seg_ws), sizeof(SegWs)) == hipSuccess;
+              hipMalloc(reinterpret_cast<void **>(&ctx->seg_ws), sizeof(SegWs)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->pred), sizeof(Prediction)) == hipSuccess;
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -593,6 +626,7 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->accepted) (void)hipFree(ctx->accepted);
     if (ctx->seed_ws) (void)hipFree(ctx->seed_ws);
     if (ctx->seg_ws) (void)hipFree(ctx->seg_ws);
+    if (ctx->pred) (void)hipFree(ctx->pred);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;

@@ -21,7 +21,7 @@ SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_st
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
-                "filter", "mean")
+                "filter", "mean", "gram_sample")
 
 
 class LaunchTime(ctypes.Structure):

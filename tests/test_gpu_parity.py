@@ -379,6 +379,40 @@ def _oracle_sequential_from_device(oracle, grads, tau):
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.parametrize("N,dtype", [(10, "bf16"), (10, "f32"), (40, "bf16")])
+def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype):
+    """Long vectors on the matrix-core path: the accept set is guessed from the first 2^22
+    elements and the Gram pass writes the mean of the guess. Here some gradients agree with the
+    seed on that prefix and oppose it on the rest, so the guess is wrong and the stand-alone
+    mean must take over; a second batch has a consistent prefix (guess right)."""
+    P = (1 << 26) + 12_345
+    gen = torch.Generator(device="cuda").manual_seed(100 + N)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    c = torch.randn(P, generator=gen, device="cuda")
+    flip = torch.ones(P, device="cuda"); flip[: 1 << 22] = -1.0
+    signs = [1, 1, -1, 1, -1] * (N // 5)
+    for twist in (True, False):
+        grads = []
+        for i in range(N):
+            z = torch.randn(P, generator=gen, device="cuda")
+            g = signs[i] * 0.4 * c + 0.9 * z
+            if twist and i in (1, 2, N - 1):
+                g = g + (flip - 1.0) * signs[i] * 0.4 * c      # opposite relation to c on the prefix only
+            grads.append(g.to(tdt))
+            del z, g
+        res = gaf.gaf_aggregate(ctx, grads, 0.95)
+        torch.cuda.synchronize()
+        ref = _oracle_sequential_from_device(oracle, grads, 0.95)
+        assert np.all(np.abs(ref[2][1:] - np.float32(0.95)) >= MARGIN)
+        check_against_oracle(res, ref, dtype)
+        if twist:
+            # the prefix alone would have decided differently for the twisted gradients
+            pre = oracle.aggregate([wl.to_host_array(g[: 1 << 22]) for g in grads], np.float32(0.95))
+            assert pre[1].tolist() != ref[1].tolist()
+        del grads, res
+
+
+@pytest.mark.timeout(600)
 def test_large_full_size(ctx, oracle):
     for seed in range(4):
         w, grads = wl.generate("large", seed, device="cuda")
