@@ -105,8 +105,7 @@ def main():
     else:
         schedule_used = "gram_first"
     # long vectors on the matrix-core path: the Gram pass also writes the mean of a guessed accept set
-    fused = (schedule_used == "gram_first" and args.schedule == "auto" and N > 8 and P >= (1 << 26)
-             and w.mode != "pairwise")
+    fused = schedule_used == "gram_first" and args.schedule == "auto" and N > 8 and P >= (1 << 26)
     if fused:
         schedule_used = "gram_first_fused_mean"
 
@@ -127,8 +126,7 @@ def main():
         else:
             if w.mode == "pairwise" and state["schedule"] != "sequential":
                 # the distance matrix and the filter share one Gram pass
-                gaf.gaf_pairwise(ctx, grads, D=D, gram=G)
-                gaf.gaf_aggregate_with_gram(ctx, grads, w.tau, G, out, mask, dist, count)
+                gaf.gaf_aggregate_with_matrix(ctx, grads, w.tau, out, mask, dist, count, D, G)
                 return
             if w.mode == "pairwise":
                 gaf.gaf_pairwise(ctx, grads, D=D)

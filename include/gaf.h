@@ -201,6 +201,19 @@ gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N
                                    uint8_t *accept_mask, float *cos_dist, int32_t *count, void *stream);
 
 /*
+ * The batch aggregation AND the all-pairs distance matrix of the same gradients
+ * in one call (Algorithm 1 + Eq. 5, and Eq. 4 over every pair as in
+ * gaf_pairwise): both come from the one Gram pass the Gram-first schedule makes
+ * anyway, including the fused mean of the AUTO schedule for long vectors.
+ *   D     DEVICE, N*N binary32 distances as in gaf_pairwise.
+ *   gram  DEVICE, N*N binary64 inner products, may be NULL.
+ * 1 <= N <= 64 (GAF_EUNSUPPORTED beyond); other arguments as in gaf_aggregate.
+ */
+gaf_status gaf_aggregate_with_matrix(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                     gaf_dtype dt, float tau, float *out, uint8_t *accept_mask,
+                                     float *cos_dist, int32_t *count, float *D, double *gram, void *stream);
+
+/*
  * Order-indifferent variant the paper sketches for the filter's dependence on
  * the seed (Sec. 3.1, last paragraph; "Order Indifference" under future
  * research): every micro-gradient takes a turn as the seed, the others being

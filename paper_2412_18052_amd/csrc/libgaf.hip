@@ -340,6 +340,8 @@ struct BatchOptions {
     float *theta = nullptr;         // non-null: fused GAF-SGD step on (theta, vel)
     float *vel = nullptr;
     float lr = 0.f, mu = 0.f, wd = 0.f;
+    float *dist_matrix = nullptr;   // non-null: also write the N x N distance matrix (and gram_out if non-null)
+    double *gram_out = nullptr;
 };
 
 template <typename T, bool kStream>
@@ -386,6 +388,12 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
+    if (opt.dist_matrix) {
+        Timed t(ctx, s, GAF_K_DISTANCE);
+        gram_to_distance_kernel<<<(N * N + kBlock - 1) / kBlock, kBlock, 0, s>>>(gram, N, opt.dist_matrix,
+                                                                                 opt.gram_out);
+    }
+    if (opt.dist_matrix && launched() != GAF_OK) return GAF_EHIP;
     MeanArgs m{};
     for (int i = 0; i < kBatchMaxN; ++i) m.rows[i] = grads[i < N ? i : 0];
     m.N = N;
@@ -706,6 +714,21 @@ gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N
     }
     BatchOptions opt;
     opt.gram = gram;
+    return gram_first_dispatch(ctx, grads, N, P, dt, tau, opt, out, accept_mask, cos_dist, count,
+                               static_cast<hipStream_t>(stream));
+}
+
+gaf_status gaf_aggregate_with_matrix(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
+                                     gaf_dtype dt, float tau, float *out, uint8_t *accept_mask,
+                                     float *cos_dist, int32_t *count, float *D, double *gram, void *stream)
+{
+    gaf_status rc = check_batch(ctx, grads, N, P, dt, out, true);
+    if (rc != GAF_OK) return rc;
+    if (!accept_mask || !cos_dist || !count || !D) return GAF_EINVAL;
+    if (N > kBatchMaxN) return GAF_EUNSUPPORTED;
+    BatchOptions opt;
+    opt.dist_matrix = D;
+    opt.gram_out = gram;
     return gram_first_dispatch(ctx, grads, N, P, dt, tau, opt, out, accept_mask, cos_dist, count,
                                static_cast<hipStream_t>(stream));
 }

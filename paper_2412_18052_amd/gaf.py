@@ -17,7 +17,8 @@ GAF_F32, GAF_BF16 = 0, 1
 
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
            "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram",
-           "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed")
+           "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed",
+           "gaf_aggregate_with_matrix")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -68,6 +69,9 @@ def load(path=None):
     lib.gaf_aggregate_with_gram.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
                                             c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
                                             c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_aggregate_with_matrix.restype = c.c_int
+    lib.gaf_aggregate_with_matrix.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
+                                              c.c_int, c.c_float] + [c.c_void_p] * 7
     lib.gaf_aggregate_best_seed.restype = c.c_int
     lib.gaf_aggregate_best_seed.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t,
                                             c.c_int, c.c_float] + [c.c_void_p] * 6
@@ -214,6 +218,20 @@ def _batch_outputs(grads, rows, out, accept_mask, cos_dist, count):
     cos_dist = torch.empty(shape, dtype=torch.float32, device=dev) if cos_dist is None else cos_dist
     count = torch.empty(1 if rows is None else rows, dtype=torch.int32, device=dev) if count is None else count
     return out, accept_mask, cos_dist, count
+
+
+def gaf_aggregate_with_matrix(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,
+                              D=None, gram=None, stream=None):
+    """Batch aggregation plus the N x N distance matrix from the same Gram pass.
+    Returns (out, accept_mask, cos_dist, count, D)."""
+    table, P, code = _grad_table(grads)
+    N = len(grads)
+    out, accept_mask, cos_dist, count = _batch_outputs(grads, None, out, accept_mask, cos_dist, count)
+    D = torch.empty((N, N), dtype=torch.float32, device=grads[0].device) if D is None else D
+    _check(load().gaf_aggregate_with_matrix(ctx.handle, table, N, P, code, float(tau), _ptr(out),
+                                            _ptr(accept_mask), _ptr(cos_dist), _ptr(count), _ptr(D),
+                                            _ptr(gram), _stream_handle(stream)), "gaf_aggregate_with_matrix")
+    return out, accept_mask, cos_dist, count, D
 
 
 def gaf_aggregate_best_seed(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,

@@ -119,6 +119,11 @@ def test_diagnostic_scaled(ctx, oracle):
     # the filter replayed on the matrix gaf_pairwise has just written
     res2 = gaf.gaf_aggregate_with_gram(ctx, dev, w.tau, gram)
     check_against_oracle(res2, ref, w.dtype)
+    # matrix and filter from one call
+    gram3 = torch.empty_like(gram)
+    res3 = gaf.gaf_aggregate_with_matrix(ctx, dev, w.tau, gram=gram3)
+    check_against_oracle(res3[:4], ref, w.dtype)
+    assert torch.equal(res3[4], D) and torch.equal(gram3, gram)
 
 
 # ------------------------------------------------------------ shapes / tails --
@@ -448,7 +453,9 @@ def test_diagnostic_full_size(ctx, oracle):
     check_against_oracle(res, ref, "f32")
     assert ref[1].tolist() == [1 if k == 0 else 0 for k in w.cluster]
     D = gaf.gaf_pairwise(ctx, grads)
-    torch.cuda.synchronize()
+    res_m = gaf.gaf_aggregate_with_matrix(ctx, grads, w.tau)       # long vectors: fused mean + matrix
+    check_against_oracle(res_m[:4], ref, "f32")
+    assert torch.equal(res_m[4], D)
     Dh = D.cpu().numpy().astype(np.float64)
     assert np.array_equal(Dh, Dh.T) and np.all(np.diag(Dh) == 0)
     assert Dh.min() >= 0 and Dh.max() <= 2
