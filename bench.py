@@ -105,7 +105,7 @@ def main():
     else:
         schedule_used = "gram_first"
     # long vectors on the matrix-core path: the Gram pass also writes the mean of a guessed accept set
-    fused = schedule_used == "gram_first" and args.schedule == "auto" and N > 8 and P >= (1 << 26)
+    fused = schedule_used == "gram_first" and args.schedule == "auto" and P >= (1 << 26)
     if fused:
         schedule_used = "gram_first_fused_mean"
 

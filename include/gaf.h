@@ -132,7 +132,7 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *               Algorithm 1 on the device, then Eq. 5 as one masked mean over
  *               the accepted gradients (c reads, one write). 2 <= N <= 64.
  *   AUTO        GRAM when 2 <= N <= 64, otherwise SEQUENTIAL. The default.
- *               For long vectors (P >= 2^26) and N > 8 AUTO additionally guesses
+ *               For long vectors (P >= 2^26) AUTO additionally guesses
  *               the accept set from the first 2^22 elements and lets the Gram pass
  *               write the mean of that guess while it has the data staged on chip;
  *               once the full inner products are known the guess is checked on the

@@ -126,6 +126,8 @@ struct SmallGramArgs {
     const void *rows[kSmallMaxN];
     size_t P;
     double *partials;     // [pairs][kMaxBlocks]
+    const Prediction *pred;   // kMean only
+    float *mean_out;
 };
 
 __host__ __device__ constexpr int small_gram_unroll(int n) { return n <= 4 ? 4 : 2; }   // 16-byte units per thread per tile
@@ -135,9 +137,15 @@ __host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlo
 // tiles first, first + stride, ... of that range; the workgroup's sums end up in
 // out[pair] for pair = 0 .. N(N+1)/2 - 1 (row-major upper triangle), written by
 // the first N(N+1)/2 threads. lo must be a multiple of 8 elements.
-template <typename T, int N, bool kStream>
+// kMean: the mean (Eq. 5) of the gradients a Prediction names is written to
+// mean_out from the registers that already hold the loaded values (see the
+// matrix-core Gram kernel for the idea); the plain filter visits in index order,
+// so adding the predicted rows in index order reproduces the stand-alone mean
+// kernel bit for bit.
+template <typename T, int N, bool kStream, bool kMean = false>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
-                                                 size_t first, size_t stride, double *out, size_t out_stride)
+                                                 size_t first, size_t stride, double *out, size_t out_stride,
+                                                 const Prediction *pred = nullptr, float *mean_out = nullptr)
 {
     constexpr int NP = N * (N + 1) / 2;
     constexpr int U = small_gram_unroll(N);
@@ -150,6 +158,20 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     double acc[NP];
 #pragma unroll
     for (int k = 0; k < NP; ++k) acc[k] = 0.0;
+
+    bool take[N];                    // kMean: is row i in the predicted accept set (uniform)
+    float inv_c = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) take[i] = false;
+    if (kMean) {
+        const int c = pred->count;
+        inv_c = 1.0f / (float)c;
+        for (int k = 0; k < c; ++k) {
+            const int idx = pred->list[k];
+#pragma unroll
+            for (int i = 0; i < N; ++i) take[i] = take[i] || idx == i;
+        }
+    }
 
     auto add = [&](const float (&x)[N]) {
         double d[N];
@@ -186,6 +208,19 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 #pragma unroll
                 for (int i = 0; i < N; ++i) x[i] = v[u][i].w;
                 add(x);
+                if (kMean) {
+                    f32x4_t m = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int i = 0; i < N; ++i)
+                        if (take[i]) {
+                            m.x += v[u][i].x;
+                            m.y += v[u][i].y;
+                            m.z += v[u][i].z;
+                            m.w += v[u][i].w;
+                        }
+                    const f32x4_t o = {m.x * inv_c, m.y * inv_c, m.z * inv_c, m.w * inv_c};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t *>(mean_out + base + size_t(u) * kBlock * 4));
+                }
             }
         } else {
             for (int u = 0; u < U; ++u)
@@ -196,6 +231,13 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 #pragma unroll
                     for (int i = 0; i < N; ++i) x[i] = load1(row[i], idx);
                     add(x);
+                    if (kMean) {
+                        float m = 0.f;
+#pragma unroll
+                        for (int i = 0; i < N; ++i)
+                            if (take[i]) m += x[i];
+                        mean_out[idx] = m * inv_c;
+                    }
                 }
         }
     }
@@ -215,11 +257,12 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     }
 }
 
-template <typename T, int N, bool kStream>
+template <typename T, int N, bool kStream, bool kMean = false>
 __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
 {
     // partials laid out [pair][kMaxBlocks]
-    gram_small_range<T, N, kStream>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x, kMaxBlocks);
+    gram_small_range<T, N, kStream, kMean>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x,
+                                           kMaxBlocks, a.pred, a.mean_out);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner

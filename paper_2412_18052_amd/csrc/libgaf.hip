@@ -291,23 +291,30 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
 template <typename T, bool kStream, int N>
 gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 {
-    gram_small_kernel<T, N, kStream><<<nb, kBlock, 0, s>>>(g);
+    if (g.mean_out)
+        gram_small_kernel<T, N, true, true><<<nb, kBlock, 0, s>>>(g);   // long vectors only: streaming loads
+    else
+        gram_small_kernel<T, N, kStream><<<nb, kBlock, 0, s>>>(g);
     return launched();
 }
 
+// With `mean_out` the launch also writes the mean of ctx->pred's accept set there.
 template <typename T, bool kStream>
-gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s)
+gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
+                      gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
 {
     SmallGramArgs g{};
     for (int i = 0; i < kSmallMaxN; ++i) g.rows[i] = grads[i < N ? i : 0];
     g.P = P;
     g.partials = ctx->gram_ws;
+    g.pred = ctx->pred;
+    g.mean_out = mean_out;
     // at most two workgroups per CU: few partial sums to combine afterwards, and the widest
     // variant (N = 8) does not fit more anyway
     const int nb = pass_blocks(P) < kSmallBlocks ? pass_blocks(P) : kSmallBlocks;
     gaf_status rc = GAF_OK;
     {
-        Timed t(ctx, s, GAF_K_GRAM);
+        Timed t(ctx, s, id);
         switch (N) {
         case 1: rc = gram_small_launch<T, kStream, 1>(g, nb, s); break;
         case 2: rc = gram_small_launch<T, kStream, 2>(g, nb, s); break;
@@ -350,12 +357,14 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                int32_t *count, hipStream_t s)
 {
     const double *gram = opt.gram;
-    // Long vectors on the matrix-core path: guess the accept set from a prefix, let the Gram pass
-    // write the mean of that guess while the data is staged in LDS, and check the guess afterwards.
-    const bool speculate = !gram && !opt.best_seed && !opt.theta && N > kSmallMaxN && P >= kSpecMinP &&
+    // Long vectors: guess the accept set from a prefix, let the Gram pass
+    // write the mean of that guess while it holds the data on chip, and check the guess afterwards.
+    const bool speculate = !gram && !opt.best_seed && !opt.theta && P >= kSpecMinP &&
                            ctx->schedule == GAF_SCHEDULE_AUTO;
+    const bool small = N <= kSmallMaxN;
     if (speculate) {
-        gaf_status rc = gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE);
+        gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE)
+                              : gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE);
         if (rc != GAF_OK) return rc;
         {
             Timed t(ctx, s, GAF_K_FILTER);
@@ -363,12 +372,13 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                            &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list);
         }
         if (launched() != GAF_OK) return GAF_EHIP;
-        rc = gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out);
+        rc = small ? gram_small<T, true>(ctx, grads, N, P, s, GAF_K_GRAM, out)
+                   : gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     } else if (!gram) {
-        const gaf_status rc = N <= kSmallMaxN ? gram_small<T, kStream>(ctx, grads, N, P, s)
-                                              : gram_all_pairs<T>(ctx, grads, N, P, s);
+        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s)
+                                    : gram_all_pairs<T>(ctx, grads, N, P, s);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     }

@@ -384,7 +384,7 @@ def _oracle_sequential_from_device(oracle, grads, tau):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("N,dtype", [(10, "bf16"), (10, "f32"), (40, "bf16")])
+@pytest.mark.parametrize("N,dtype", [(10, "bf16"), (10, "f32"), (40, "bf16"), (5, "f32"), (5, "bf16")])
 def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype):
     """Long vectors on the matrix-core path: the accept set is guessed from the first 2^22
     elements and the Gram pass writes the mean of the guess. Here some gradients agree with the
@@ -401,7 +401,7 @@ def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype):
         for i in range(N):
             z = torch.randn(P, generator=gen, device="cuda")
             g = signs[i] * 0.4 * c + 0.9 * z
-            if twist and i in (1, 2, N - 1):
+            if twist and i in (1, 2, N - 1):   # (for N = 5: gradients 1, 2 and 4)
                 g = g + (flip - 1.0) * signs[i] * 0.4 * c      # opposite relation to c on the prefix only
             grads.append(g.to(tdt))
             del z, g
@@ -410,6 +410,15 @@ def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype):
         ref = _oracle_sequential_from_device(oracle, grads, 0.95)
         assert np.all(np.abs(ref[2][1:] - np.float32(0.95)) >= MARGIN)
         check_against_oracle(res, ref, dtype)
+        if ctx.schedule_name == "auto":
+            # whether the guess was right or wrong, the result equals the two-pass schedule's bit for bit
+            gaf.gaf_set_schedule(ctx, "gram")
+            two_pass = gaf.gaf_aggregate(ctx, grads, 0.95)
+            gaf.gaf_set_schedule(ctx, "auto")
+            torch.cuda.synchronize()
+            for x, y in zip(res, two_pass):
+                assert torch.equal(x, y)
+            del two_pass
         if twist:
             # the prefix alone would have decided differently for the twisted gradients
             pre = oracle.aggregate([wl.to_host_array(g[: 1 << 22]) for g in grads], np.float32(0.95))
