@@ -5,8 +5,8 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic
 micro-gradients already resident in HBM: a full gaf_aggregate (batch
-workloads), N gaf_step calls (streaming), or gaf_pairwise followed by
-gaf_aggregate (diagnostic). Prints ONE JSON line.
+workloads), N gaf_step calls (streaming), or gaf_aggregate_with_matrix
+(diagnostic: distance matrix plus filter). Prints ONE JSON line.
 
 value = effective HBM GB/s = (bytes the method itself must move) / time:
     per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted (write it),
