@@ -62,6 +62,7 @@ def main():
                     help="capture one step in a HIP graph and time its replays (launch-bound sizes)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--P", type=int, default=None, help="override the vector length")
+    ap.add_argument("--N", type=int, default=None, help="override the number of micro-gradients")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
                     help="before anything else run one plain copy of ELEMS binary32 elements through "
                          "the library (a single-gradient batch: reads 4*ELEMS bytes, writes 4*ELEMS): "
@@ -92,7 +93,7 @@ def main():
         del src
 
     t0 = time.time()
-    w, grads = wl.generate(args.workload, args.seed, P=args.P, device="cuda")
+    w, grads = wl.generate(args.workload, args.seed, P=args.P, N=args.N, device="cuda")
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     P, N, s = w.P, w.N, w.elem_bytes
