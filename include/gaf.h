@@ -136,8 +136,12 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *               the accept set from the first 2^22 elements and lets the Gram pass
  *               write the mean of that guess while it has the data staged on chip;
  *               once the full inner products are known the guess is checked on the
- *               device, and only a wrong guess costs the separate mean pass. The
- *               result is the same either way, bit for bit.
+ *               device, and only a wrong guess costs the separate mean pass. When
+ *               the guess names only a few gradients (fewer than a break-even
+ *               count between 2 and 10 that depends on dtype and N) the Gram pass
+ *               stays read-only and the separate mean pass, cheap for so few
+ *               gradients, does the work. The result is the same in every case,
+ *               bit for bit.
  * Explicit GRAM with N outside its range returns GAF_EUNSUPPORTED.
  */
 typedef enum {

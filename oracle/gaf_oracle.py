@@ -21,12 +21,18 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gaf_oracle.c")
 _LIB = os.path.join(_HERE, "libgaf_oracle.so")
+# The mutation test of the pins (tests/test_oracle_mutants.py) loads a private copy of this
+# module and points it at a deliberately broken build of the oracle, expecting the pins to
+# fail; nothing else sets it.
+_OVERRIDE = None
 
 F32, BF16 = 0, 1
 
 
 def build(force=False):
     """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB

@@ -128,6 +128,7 @@ struct SmallGramArgs {
     double *partials;     // [pairs][kMaxBlocks]
     const Prediction *pred;   // kMean only
     float *mean_out;
+    int min_count;
 };
 
 __host__ __device__ constexpr int small_gram_unroll(int n) { return n <= 4 ? 4 : 2; }   // 16-byte units per thread per tile
@@ -145,7 +146,8 @@ __host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlo
 template <typename T, int N, bool kStream, bool kMean = false>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
                                                  size_t first, size_t stride, double *out, size_t out_stride,
-                                                 const Prediction *pred = nullptr, float *mean_out = nullptr)
+                                                 const Prediction *pred = nullptr, float *mean_out = nullptr,
+                                                 int min_count = 0)
 {
     constexpr int NP = N * (N + 1) / 2;
     constexpr int U = small_gram_unroll(N);
@@ -163,6 +165,7 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     float inv_c = 0.f;
 #pragma unroll
     for (int i = 0; i < N; ++i) take[i] = false;
+    const bool write_mean = kMean && pred->count >= min_count;   // see GramArgs::min_count
     if (kMean) {
         const int c = pred->count;
         inv_c = 1.0f / (float)c;
@@ -208,7 +211,7 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 #pragma unroll
                 for (int i = 0; i < N; ++i) x[i] = v[u][i].w;
                 add(x);
-                if (kMean) {
+                if (kMean && write_mean) {
                     f32x4_t m = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int i = 0; i < N; ++i)
@@ -231,7 +234,7 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 #pragma unroll
                     for (int i = 0; i < N; ++i) x[i] = load1(row[i], idx);
                     add(x);
-                    if (kMean) {
+                    if (kMean && write_mean) {
                         float m = 0.f;
 #pragma unroll
                         for (int i = 0; i < N; ++i)
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
 {
     // partials laid out [pair][kMaxBlocks]
     gram_small_range<T, N, kStream, kMean>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x,
-                                           kMaxBlocks, a.pred, a.mean_out);
+                                           kMaxBlocks, a.pred, a.mean_out, a.min_count);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner
@@ -296,8 +299,9 @@ struct MeanArgs {
     const State *st;                // st->count = c
     float *out;                     // may be NULL in the fused-optimizer form
     size_t P;
-    const Prediction *pred;         // non-NULL: `out` already holds the mean of this predicted accept set;
-                                    // the launch has work to do only if the prediction was wrong
+    const Prediction *pred;         // non-NULL: `out` already holds the mean of this predicted accept set
+    int pred_min_count;             // (if it names at least this many gradients); the launch has work to
+                                    // do only if that mean was not written or the prediction was wrong
     // fused GAF-SGD step (kSgd): parameters and momentum buffer, in place
     float *theta, *vel;
     float lr, mu, wd;
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
     __shared__ int32_t list[kBatchMaxN];
     const int c = a.st->count;
     if (a.pred) {
-        bool same = a.pred->count == c;
+        bool same = a.pred->count == c && c >= a.pred_min_count;
         for (int k = 0; same && k < c; ++k) same = a.pred->list[k] == a.accepted_list[k];
         if (same) return;           // the fused pass already wrote exactly this mean
     }

@@ -85,6 +85,9 @@ struct GramArgs {
     // kMean only: the mean of the predicted accept set is formed from the staged data and written here
     const Prediction *pred;
     float *out;
+    int min_count;                // ... but only if the prediction names at least this many gradients:
+                                  // with few accepted the stand-alone mean is cheaper than mixing
+                                  // writes into this pass (written bytes are the expensive ones)
 };
 
 // 16 bytes of a row starting at element p, element-wise and zero past the end.
@@ -186,8 +189,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         row_table[threadIdx.x] = p;
     }
     int c_pred = 0;
+    bool write_mean = false;
     if (kMean) {
         c_pred = a.pred->count;
+        write_mean = c_pred >= a.min_count;
         if (int(threadIdx.x) < c_pred) pred_rows[threadIdx.x] = a.pred->list[threadIdx.x];
     }
     __syncthreads();
@@ -336,7 +341,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         while (s + G < nfull) {
             gload(s + G);              // in flight during the MFMAs below
             compute(buf);
-            if (kMean) mean_stage(buf, s);
+            if (kMean && write_mean) mean_stage(buf, s);
             if (++since_flush == kGramFlush) {
                 since_flush = 0;
                 flush();
@@ -347,7 +352,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
             s += G;
         }
         compute(buf);
-        if (kMean) mean_stage(buf, s);
+        if (kMean && write_mean) mean_stage(buf, s);
     }
     // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
     if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
@@ -356,7 +361,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         lstore(0);
         __syncthreads();
         compute(0);
-        if (kMean) mean_stage(0, nfull);
+        if (kMean && write_mean) mean_stage(0, nfull);
     }
     flush();
 

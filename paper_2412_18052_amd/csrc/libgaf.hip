@@ -207,6 +207,19 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
     return launched();
 }
 
+// Smallest predicted accept count for which the Gram pass writes the mean itself. Mixing the
+// 4 P written bytes into the reading pass added 0.6 to 2.5 ms to the measured calls (batches of
+// 32 GB), nearly independent of the count c, while the stand-alone mean costs (c s + 4) P bytes
+// at about 5.2 TB/s; below these measured break-even counts the stand-alone mean is the cheaper
+// one (by up to 15% of the call at c = 1). groups = 0 means the small-batch (N <= 8) kernel.
+template <typename T>
+constexpr int fused_min_count(int groups)
+{
+    constexpr int bf16_min[5] = {2, 4, 6, 8, 10};
+    constexpr int f32_min[5] = {2, 4, 7, 7, 7};
+    return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
+}
+
 // Enqueues the Gram kernel for up to four 16-row groups (global group indices in
 // `groups`, -1 = absent) and the ordered combine of its per-workgroup tiles into
 // ctx->gram_full (leading dimension N).
@@ -229,6 +242,7 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     g.ws = ctx->gram_ws;
     g.pred = ctx->pred;
     g.out = mean_out;
+    g.min_count = fused_min_count<T>(NG);
     {
         Timed t(ctx, s, id);
         if (mean_out && kMode == kFull)
@@ -309,6 +323,7 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
     g.partials = ctx->gram_ws;
     g.pred = ctx->pred;
     g.mean_out = mean_out;
+    g.min_count = fused_min_count<T>(0);
     // at most two workgroups per CU: few partial sums to combine afterwards, and the widest
     // variant (N = 8) does not fit more anyway
     const int nb = pass_blocks(P) < kSmallBlocks ? pass_blocks(P) : kSmallBlocks;
@@ -412,6 +427,7 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     m.out = out;
     m.P = P;
     m.pred = speculate ? ctx->pred : nullptr;
+    m.pred_min_count = fused_min_count<T>(small ? 0 : (N + 15) / 16);
     m.theta = opt.theta;
     m.vel = opt.vel;
     m.lr = opt.lr;

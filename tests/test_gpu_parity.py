@@ -384,18 +384,22 @@ def _oracle_sequential_from_device(oracle, grads, tau):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("N,dtype", [(10, "bf16"), (10, "f32"), (40, "bf16"), (5, "f32"), (5, "bf16")])
-def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype):
+@pytest.mark.parametrize("N,dtype,pattern", [(10, "bf16", "mixed"), (10, "f32", "mixed"), (40, "bf16", "mixed"),
+                                             (5, "f32", "mixed"), (5, "bf16", "mixed"),
+                                             (10, "bf16", "few"), (10, "f32", "few"), (5, "f32", "few")])
+def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
     """Long vectors on the matrix-core path: the accept set is guessed from the first 2^22
     elements and the Gram pass writes the mean of the guess. Here some gradients agree with the
     seed on that prefix and oppose it on the rest, so the guess is wrong and the stand-alone
-    mean must take over; a second batch has a consistent prefix (guess right)."""
+    mean must take over; a second batch has a consistent prefix (guess right). With the "few"
+    pattern only one gradient in five agrees with the seed: below a break-even accept count the
+    Gram pass leaves the mean to the stand-alone kernel even when the guess is right."""
     P = (1 << 26) + 12_345
     gen = torch.Generator(device="cuda").manual_seed(100 + N)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     c = torch.randn(P, generator=gen, device="cuda")
     flip = torch.ones(P, device="cuda"); flip[: 1 << 22] = -1.0
-    signs = [1, 1, -1, 1, -1] * (N // 5)
+    signs = ([1, 1, -1, 1, -1] if pattern == "mixed" else [1, -1, -1, -1, -1]) * (N // 5)
     for twist in (True, False):
         grads = []
         for i in range(N):

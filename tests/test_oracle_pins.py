@@ -233,7 +233,10 @@ def test_pairwise_properties_and_gram_consistency(oracle):
     assert np.array_equal(D, D.T) and np.all(np.diag(D) == 0.0)
     assert D.min() >= 0.0 and D.max() <= 2.0
     X = np.stack(a).astype(np.float64)
-    np.testing.assert_allclose(G, X @ X.T, rtol=1e-12)            # BLAS contraction
+    # BLAS contraction. Two summation orders of an inner product differ by a multiple of
+    # eps |x|.|y| (not of the result, which cancellation can make small): bound by |x| |y|.
+    nrm = np.sqrt(np.diag(G))
+    assert np.all(np.abs(G - X @ X.T) <= 1e-13 * np.outer(nrm, nrm))
     out, mask, dist, c = oracle.aggregate(a, f32(w.tau))
     # the sequential distances follow from G alone: with A the accepted set so far,
     # g_i . sum = sum_{j in A} G_ij, |sum|^2 = sum_{j,k in A} G_jk, |g_i|^2 = G_ii
