@@ -133,15 +133,23 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *               the accepted gradients (c reads, one write). 2 <= N <= 64.
  *   AUTO        GRAM when 2 <= N <= 64, otherwise SEQUENTIAL. The default.
  *               For long vectors (P >= 2^26) AUTO additionally guesses
- *               the accept set from the first 2^22 elements and lets the Gram pass
+ *               the accept set from a sample of 2^22 elements of every gradient
+ *               (256 runs of 2^14 consecutive elements; run r starts at element
+ *               r * S, S = P / 256 rounded down to a multiple of 2^14, so the
+ *               runs spread over all parts of the vector) and lets the Gram pass
  *               write the mean of that guess while it has the data staged on chip;
  *               once the full inner products are known the guess is checked on the
  *               device, and only a wrong guess costs the separate mean pass. When
  *               the guess names only a few gradients (fewer than a break-even
  *               count between 2 and 10 that depends on dtype and N) the Gram pass
  *               stays read-only and the separate mean pass, cheap for so few
- *               gradients, does the work. The result is the same in every case,
- *               bit for bit.
+ *               gradients, does the work. A context also keeps a record of its
+ *               guesses on the device: a written guess that proves wrong stops
+ *               the writing for the next `penalty` calls (1 at first, doubling
+ *               per miss up to 64, halving per hit), so callers whose distances
+ *               sit close to tau stop paying for wrong guesses; nothing of this
+ *               synchronises with the host. The result is the same in every
+ *               case, bit for bit.
  * Explicit GRAM with N outside its range returns GAF_EUNSUPPORTED.
  */
 typedef enum {
@@ -150,7 +158,18 @@ typedef enum {
     GAF_SCHEDULE_GRAM = 2
 } gaf_schedule;
 
+/* Also clears the context's record of guesses (the next batch call enqueues the clearing). */
 gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule);
+
+/*
+ * Diagnostics of AUTO's fused mean: copies the context's record of guesses to
+ * the HOST array record[4] = { this call's Gram pass wrote the mean of its guess
+ * (0/1), the guess was right and the result was left in place (0/1), calls still
+ * to go without writing, penalty the next wrong guess will impose }.
+ * Unlike every other call this one WAITS for the device to become idle first;
+ * it is meant for tests and tuning, not for the training loop.
+ */
+gaf_status gaf_fused_mean_record(gaf_ctx *ctx, int32_t record[4]);
 
 /*
  * Streaming form: one visit of Algorithm 1's inner loop for a gradient that

@@ -59,9 +59,23 @@ __device__ __forceinline__ int run_filter(const double *gram, int N, int seed, f
     return c;
 }
 
+// What a filter launch does with the context's Prediction.
+enum : int { kSpecNone = 0, kSpecGuess = 1, kSpecVerify = 2 };
+
+// kSpecGuess (run on the inner products of a sample; accepted_list = pred->list): records the
+// guessed accept set and decides whether this call's Gram pass writes its mean -- only if the
+// guess names at least min_count gradients (below that the stand-alone mean is cheaper than
+// mixing writes into the reading pass) and no backoff from an earlier wrong guess is running.
+// kSpecVerify (run on the full inner products): compares the guess with the accept set just
+// computed, tells the mean kernel whether the result is already in place, and keeps the record:
+// a written guess that was wrong stops writing for `penalty` calls and doubles the penalty, a
+// right one halves it; a call that did not write counts the backoff down. All on the device, so
+// a caller whose gradients sit close to the threshold stops paying for wrong guesses without
+// ever synchronising.
 __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
                                                     uint8_t *mask, float *cos_dist, int32_t *count,
-                                                    int32_t *accepted_list)
+                                                    int32_t *accepted_list, int spec = kSpecNone,
+                                                    Prediction *pred = nullptr, int min_count = 0)
 {
     const int c = run_filter(gram, N, 0, tau, mask, cos_dist, accepted_list);
     if (threadIdx.x == 0) {
@@ -70,6 +84,40 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
         st->accept = 0;
         st->seed = 0;
     }
+    if (spec == kSpecGuess) {
+        if (threadIdx.x == 0) {
+            pred->write = (c >= min_count && pred->backoff == 0) ? 1 : 0;
+            pred->valid = 0;
+        }
+    } else if (spec == kSpecVerify) {
+        if (threadIdx.x == 0) {      // the thread that wrote accepted_list above
+            bool same = pred->count == c;
+            for (int k = 0; same && k < c; ++k) same = pred->list[k] == accepted_list[k];
+            int penalty = pred->penalty < 1 ? 1 : pred->penalty;
+            if (pred->write) {
+                if (same) {
+                    penalty = penalty > 1 ? penalty / 2 : 1;
+                } else {
+                    pred->backoff = penalty;
+                    penalty = 2 * penalty < kSpecMaxPenalty ? 2 * penalty : kSpecMaxPenalty;
+                }
+            } else if (pred->backoff > 0) {
+                pred->backoff -= 1;
+            }
+            pred->penalty = penalty;
+            pred->valid = (pred->write && same) ? 1 : 0;
+        }
+    }
+}
+
+// Forgets the record of earlier guesses (a fresh context, or the schedule was set anew).
+__global__ void prediction_reset_kernel(Prediction *pred)
+{
+    pred->count = 0;
+    pred->write = 0;
+    pred->valid = 0;
+    pred->backoff = 0;
+    pred->penalty = 1;
 }
 
 // Order-indifferent variant (Sec. 3.1, last paragraph): workgroup s replays the
@@ -128,7 +176,7 @@ struct SmallGramArgs {
     double *partials;     // [pairs][kMaxBlocks]
     const Prediction *pred;   // kMean only
     float *mean_out;
-    int min_count;
+    size_t chunk_stride;      // non-zero: sampling launch, see gram_small_range
 };
 
 __host__ __device__ constexpr int small_gram_unroll(int n) { return n <= 4 ? 4 : 2; }   // 16-byte units per thread per tile
@@ -147,11 +195,13 @@ template <typename T, int N, bool kStream, bool kMean = false>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
                                                  size_t first, size_t stride, double *out, size_t out_stride,
                                                  const Prediction *pred = nullptr, float *mean_out = nullptr,
-                                                 int min_count = 0)
+                                                 size_t chunk_stride = 0)
 {
     constexpr int NP = N * (N + 1) / 2;
     constexpr int U = small_gram_unroll(N);
     constexpr size_t tile = small_gram_tile(N);
+    constexpr size_t kTilesPerChunk = kSampleChunk / tile;
+    static_assert(kSampleChunk % tile == 0, "a sample run is a whole number of tiles");
     __shared__ double lds[NP][kWaves];
 
     const T *row[N];
@@ -165,7 +215,7 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     float inv_c = 0.f;
 #pragma unroll
     for (int i = 0; i < N; ++i) take[i] = false;
-    const bool write_mean = kMean && pred->count >= min_count;   // see GramArgs::min_count
+    const bool write_mean = kMean && pred->write != 0;
     if (kMean) {
         const int c = pred->count;
         inv_c = 1.0f / (float)c;
@@ -189,7 +239,11 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 
     const size_t ntiles = (hi - lo + tile - 1) / tile;
     for (size_t t = first; t < ntiles; t += stride) {
-        const size_t base = lo + t * tile + size_t(threadIdx.x) * 4;
+        // sampling launch (chunk_stride != 0): [lo, hi) indexes the sample, whose run r of
+        // kSampleChunk elements starts at element r * chunk_stride of the vectors
+        const size_t tile_at = chunk_stride ? (t / kTilesPerChunk) * chunk_stride + (t % kTilesPerChunk) * tile
+                                            : t * tile;
+        const size_t base = lo + tile_at + size_t(threadIdx.x) * 4;
         if (lo + (t + 1) * tile <= hi) {
             float4 v[U][N];
 #pragma unroll
@@ -265,7 +319,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
 {
     // partials laid out [pair][kMaxBlocks]
     gram_small_range<T, N, kStream, kMean>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x,
-                                           kMaxBlocks, a.pred, a.mean_out, a.min_count);
+                                           kMaxBlocks, a.pred, a.mean_out, a.chunk_stride);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner
@@ -299,9 +353,8 @@ struct MeanArgs {
     const State *st;                // st->count = c
     float *out;                     // may be NULL in the fused-optimizer form
     size_t P;
-    const Prediction *pred;         // non-NULL: `out` already holds the mean of this predicted accept set
-    int pred_min_count;             // (if it names at least this many gradients); the launch has work to
-                                    // do only if that mean was not written or the prediction was wrong
+    const Prediction *pred;         // non-NULL: if pred->valid, `out` already holds the result (written by
+                                    // the Gram pass for a guessed accept set that proved right)
     // fused GAF-SGD step (kSgd): parameters and momentum buffer, in place
     float *theta, *vel;
     float lr, mu, wd;
@@ -416,11 +469,7 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
     __shared__ const void *table[kBatchMaxN];
     __shared__ int32_t list[kBatchMaxN];
     const int c = a.st->count;
-    if (a.pred) {
-        bool same = a.pred->count == c && c >= a.pred_min_count;
-        for (int k = 0; same && k < c; ++k) same = a.pred->list[k] == a.accepted_list[k];
-        if (same) return;           // the fused pass already wrote exactly this mean
-    }
+    if (a.pred && a.pred->valid) return;      // the fused pass already wrote exactly this mean
     if (threadIdx.x < kBatchMaxN) {
         table[threadIdx.x] = a.rows[threadIdx.x];
         list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;

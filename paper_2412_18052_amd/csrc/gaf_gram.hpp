@@ -40,6 +40,7 @@ constexpr int kGramBlocks = 512;        // workgroups per launch (fixed: the sum
 constexpr int kGramTile = 16 * 16;      // entries per tile
 constexpr int kGramMaxTiles = 10;       // 4 groups: 4 diagonal + 6 off-diagonal tiles
 constexpr int kGramPad = 4;             // LDS row padding, 32-bit words
+constexpr size_t kSampleChunk = size_t(1) << 14;   // elements per contiguous run of a sampling launch
 
 // Which tiles a launch computes.
 //   kFull : every pair (a <= b) of the NG groups               -> NG (NG + 1) / 2 tiles
@@ -70,12 +71,20 @@ struct TileList {
 // 3-4 KB of loads in flight per wavefront whatever the row count.
 __host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 8 : ng == 2 ? 4 : 2; }
 
-// An accept set guessed before the full inner products are known (from a prefix
-// of the vectors): which gradients Algorithm 1 will probably accept, in visiting order.
+// An accept set guessed before the full inner products are known (from a sample
+// of the vectors): which gradients Algorithm 1 will probably accept, in visiting order,
+// and what is done with the guess. Lives in device memory for the context's lifetime:
+// the last two fields carry the record of earlier guesses from call to call.
 struct Prediction {
     int32_t count;
     int32_t list[kGramRows];
+    int32_t write;     // this call's Gram pass writes the mean of the guess (set by the sample's filter)
+    int32_t valid;     // ... and the guess was right: the result is in place (set by the full filter)
+    int32_t backoff;   // calls left during which no guess is written, after a wrong one
+    int32_t penalty;   // backoff imposed by the next wrong guess: doubles per miss up to kSpecMaxPenalty,
+                       // halves per hit; 0 = never used, treated as 1
 };
+constexpr int kSpecMaxPenalty = 64;
 
 struct GramArgs {
     const void *rows[kGramRows];  // DEVICE pointers, group g = rows[16 g .. 16 g + 15]; never NULL: rows past
@@ -85,9 +94,11 @@ struct GramArgs {
     // kMean only: the mean of the predicted accept set is formed from the staged data and written here
     const Prediction *pred;
     float *out;
-    int min_count;                // ... but only if the prediction names at least this many gradients:
-                                  // with few accepted the stand-alone mean is cheaper than mixing
-                                  // writes into this pass (written bytes are the expensive ones)
+    // kMean launches write the mean only if pred->write says so.
+    // Sampling launches read runs of 2^chunk_shift stages, run r starting at element r * chunk_stride;
+    // an ordinary launch has chunk_shift = 62 (one run that never ends) and chunk_stride = 0.
+    int chunk_shift;
+    size_t chunk_stride;
 };
 
 // 16 bytes of a row starting at element p, element-wise and zero past the end.
@@ -192,7 +203,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     bool write_mean = false;
     if (kMean) {
         c_pred = a.pred->count;
-        write_mean = c_pred >= a.min_count;
+        write_mean = a.pred->write != 0;
         if (int(threadIdx.x) < c_pred) pred_rows[threadIdx.x] = a.pred->list[threadIdx.x];
     }
     __syncthreads();
@@ -223,9 +234,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         for (int v = 0; v < 4; ++v) tot[t][v] = 0.0;
     }
 
+    const int chunk_shift = a.chunk_shift;
+    const size_t chunk_stride = a.chunk_stride;
+    auto stage_base = [&](size_t s) {      // first element of stage s (uniform)
+        return (s >> chunk_shift) * chunk_stride + (s & ((size_t(1) << chunk_shift) - 1)) * kStageElems;
+    };
     u32x4_t pre[NG][M];
     auto gload = [&](size_t s) {
-        const size_t e0 = s * kStageElems + size_t(l16) * kElem16;
+        const size_t e0 = stage_base(s) + size_t(l16) * kElem16;
 #pragma unroll
         for (int j = 0; j < NG; ++j)
 #pragma unroll

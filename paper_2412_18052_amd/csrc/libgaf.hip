@@ -25,7 +25,8 @@ struct gaf_ctx {
     int32_t *accepted;   // device, [max_N] indices of accepted gradients (Gram-first schedule)
     SeedWs *seed_ws;     // device, per-seed filter runs (order-indifferent variant)
     SegWs *seg_ws;       // device, per-bucket filter outcomes (bucketed filtering)
-    Prediction *pred;    // device, accept set predicted from a prefix (fused mean)
+    Prediction *pred;    // device, accept set predicted from a sample (fused mean) and the record of earlier guesses
+    bool pred_reset;     // that record is to be cleared by the next call that guesses
     gaf_schedule schedule;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
@@ -224,10 +225,16 @@ constexpr int fused_min_count(int groups)
 // `groups`, -1 = absent) and the ordered combine of its per-workgroup tiles into
 // ctx->gram_full (leading dimension N).
 // With `mean_out` the launch also writes the mean of ctx->pred's accept set there (kFull only).
+// With `chunk_stride` the launch reads a sample instead: P / kSampleChunk runs of kSampleChunk
+// elements, run r starting at element r * chunk_stride of every gradient.
 template <typename T, int NG, int kMode>
 gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, const int (&groups)[4],
-                       hipStream_t s, gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
+                       hipStream_t s, gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr,
+                       size_t chunk_stride = 0)
 {
+    constexpr size_t kStagesPerChunk = kSampleChunk / (size_t(256) * gram_stage_m(NG) / sizeof(T));
+    static_assert(kStagesPerChunk >= 1 && (kStagesPerChunk & (kStagesPerChunk - 1)) == 0, "power of two");
+    if (chunk_stride && (mean_out || P % kSampleChunk)) return GAF_EINVAL;
     typedef TileList<NG, kMode> Tiles;
     GramArgs g{};
     GramFinalArgs f{};
@@ -242,7 +249,10 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     g.ws = ctx->gram_ws;
     g.pred = ctx->pred;
     g.out = mean_out;
-    g.min_count = fused_min_count<T>(NG);
+    g.chunk_shift = 62;
+    if (chunk_stride)
+        for (g.chunk_shift = 0; (size_t(1) << g.chunk_shift) < kStagesPerChunk;) ++g.chunk_shift;
+    g.chunk_stride = chunk_stride;
     {
         Timed t(ctx, s, id);
         if (mean_out && kMode == kFull)
@@ -273,7 +283,7 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
 // `mean_out` (N <= 64 only): see gram_launch.
 template <typename T>
 gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
-                          gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
+                          gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0)
 {
     const int ng = (N + 15) / 16;
     for (int g0 = 0; g0 < ng; g0 += 4) {
@@ -281,10 +291,10 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
         const int groups[4] = {g0, n > 1 ? g0 + 1 : -1, n > 2 ? g0 + 2 : -1, n > 3 ? g0 + 3 : -1};
         gaf_status rc = GAF_OK;
         switch (n) {
-        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
-        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
-        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
-        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s, id, mean_out); break;
+        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
+        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
+        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
+        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
         }
         if (rc != GAF_OK) return rc;
     }
@@ -315,15 +325,16 @@ gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 // With `mean_out` the launch also writes the mean of ctx->pred's accept set there.
 template <typename T, bool kStream>
 gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
-                      gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr)
+                      gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0)
 {
+    if (chunk_stride && (mean_out || P % kSampleChunk)) return GAF_EINVAL;
     SmallGramArgs g{};
     for (int i = 0; i < kSmallMaxN; ++i) g.rows[i] = grads[i < N ? i : 0];
     g.P = P;
     g.partials = ctx->gram_ws;
     g.pred = ctx->pred;
     g.mean_out = mean_out;
-    g.min_count = fused_min_count<T>(0);
+    g.chunk_stride = chunk_stride;
     // at most two workgroups per CU: few partial sums to combine afterwards, and the widest
     // variant (N = 8) does not fit more anyway
     const int nb = pass_blocks(P) < kSmallBlocks ? pass_blocks(P) : kSmallBlocks;
@@ -350,10 +361,19 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
 }
 
 // Fused mean (see gram_kernel's kMean): used from this vector length up, with the accept set
-// guessed from this many leading elements. The guess costs N * kSpecSample elements of extra
-// reading (under 1 % at kSpecMinP); a wrong guess costs one stand-alone mean pass.
+// guessed from a sample of this many elements of every gradient, taken as evenly spaced runs of
+// kSampleChunk elements (the parts of a model's gradient differ, so a prefix would be a poor
+// sample). The guess costs N * kSpecSample elements of extra reading (under 1 % at kSpecMinP);
+// a wrong guess costs one stand-alone mean pass.
 constexpr size_t kSpecSample = size_t(1) << 22;
 constexpr size_t kSpecMinP = size_t(1) << 26;
+
+// Distance in elements between the starts of consecutive runs of the sample for vectors of
+// length P >= kSpecMinP: the runs spread over the whole vector, the last one ends inside it.
+constexpr size_t spec_chunk_stride(size_t P)
+{
+    return P / (kSpecSample / kSampleChunk) / kSampleChunk * kSampleChunk;
+}
 
 // Variations of the Gram-first batch call.
 struct BatchOptions {
@@ -372,19 +392,26 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                int32_t *count, hipStream_t s)
 {
     const double *gram = opt.gram;
-    // Long vectors: guess the accept set from a prefix, let the Gram pass
+    // Long vectors: guess the accept set from a sample, let the Gram pass
     // write the mean of that guess while it holds the data on chip, and check the guess afterwards.
     const bool speculate = !gram && !opt.best_seed && !opt.theta && P >= kSpecMinP &&
                            ctx->schedule == GAF_SCHEDULE_AUTO;
     const bool small = N <= kSmallMaxN;
     if (speculate) {
-        gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE)
-                              : gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE);
+        if (ctx->pred_reset) {
+            prediction_reset_kernel<<<1, 1, 0, s>>>(ctx->pred);
+            if (launched() != GAF_OK) return GAF_EHIP;
+            ctx->pred_reset = false;
+        }
+        const size_t cs = spec_chunk_stride(P);
+        gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs)
+                              : gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs);
         if (rc != GAF_OK) return rc;
         {
             Timed t(ctx, s, GAF_K_FILTER);
             filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, &ctx->seed_ws->mask[0][0],
-                                           &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list);
+                                           &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list,
+                                           kSpecGuess, ctx->pred, fused_min_count<T>(small ? 0 : (N + 15) / 16));
         }
         if (launched() != GAF_OK) return GAF_EHIP;
         rc = small ? gram_small<T, true>(ctx, grads, N, P, s, GAF_K_GRAM, out)
@@ -410,7 +437,8 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         }
     } else {
         Timed t(ctx, s, GAF_K_FILTER);
-        filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted);
+        filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted,
+                                       speculate ? kSpecVerify : kSpecNone, ctx->pred);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     if (opt.dist_matrix) {
@@ -427,7 +455,6 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     m.out = out;
     m.P = P;
     m.pred = speculate ? ctx->pred : nullptr;
-    m.pred_min_count = fused_min_count<T>(small ? 0 : (N + 15) / 16);
     m.theta = opt.theta;
     m.vel = opt.vel;
     m.lr = opt.lr;
@@ -622,6 +649,7 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->prof_on = false;
     ctx->prof_cap = 0;
     ctx->schedule = GAF_SCHEDULE_AUTO;
+    ctx->pred_reset = false;
     const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
     bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
@@ -636,6 +664,7 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
               hipMalloc(reinterpret_cast<void **>(&ctx->pred), sizeof(Prediction)) == hipSuccess;
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
+    ok = ok && hipMemset(ctx->pred, 0, sizeof(Prediction)) == hipSuccess;
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     (void)hipSetDevice(prev);
     if (!ok) {
@@ -839,6 +868,26 @@ gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule)
         schedule != GAF_SCHEDULE_GRAM)
         return GAF_EINVAL;
     ctx->schedule = schedule;
+    ctx->pred_reset = true;
+    return GAF_OK;
+}
+
+gaf_status gaf_fused_mean_record(gaf_ctx *ctx, int32_t record[4])
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!record) return GAF_EINVAL;
+    Prediction h;
+    if (hipDeviceSynchronize() != hipSuccess ||
+        hipMemcpy(&h, ctx->pred, sizeof h, hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return GAF_EHIP;
+    }
+    if (ctx->pred_reset) h.write = h.valid = h.backoff = h.penalty = 0;   // cleared, not yet on the device
+    record[0] = h.write;
+    record[1] = h.valid;
+    record[2] = h.backoff;
+    record[3] = h.penalty < 1 ? 1 : h.penalty;
     return GAF_OK;
 }
 

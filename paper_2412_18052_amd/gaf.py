@@ -18,7 +18,7 @@ GAF_F32, GAF_BF16 = 0, 1
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
            "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram",
            "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed",
-           "gaf_aggregate_with_matrix")
+           "gaf_aggregate_with_matrix", "gaf_fused_mean_record")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -85,6 +85,8 @@ def load(path=None):
                                           [c.c_void_p] * 5
     lib.gaf_set_schedule.restype = c.c_int
     lib.gaf_set_schedule.argtypes = [c.c_void_p, c.c_int]
+    lib.gaf_fused_mean_record.restype = c.c_int
+    lib.gaf_fused_mean_record.argtypes = [c.c_void_p, c.POINTER(c.c_int32)]
     lib.gaf_profile_begin.restype = c.c_int
     lib.gaf_profile_begin.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_end.restype = c.c_int
@@ -173,6 +175,13 @@ def gaf_set_schedule(ctx, schedule):
     """schedule: "auto" | "sequential" | "gram" (or the integer code)."""
     code = SCHEDULES[schedule] if isinstance(schedule, str) else int(schedule)
     _check(load().gaf_set_schedule(ctx.handle, code), "gaf_set_schedule")
+
+
+def gaf_fused_mean_record(ctx):
+    """Returns {write, valid, backoff, penalty} (waits for the device; diagnostics only)."""
+    rec = (ctypes.c_int32 * 4)()
+    _check(load().gaf_fused_mean_record(ctx.handle, rec), "gaf_fused_mean_record")
+    return dict(zip(("write", "valid", "backoff", "penalty"), (int(v) for v in rec)))
 
 
 def gaf_aggregate(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, count=None,

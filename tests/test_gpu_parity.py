@@ -388,33 +388,58 @@ def _oracle_sequential_from_device(oracle, grads, tau):
                                              (5, "f32", "mixed"), (5, "bf16", "mixed"),
                                              (10, "bf16", "few"), (10, "f32", "few"), (5, "f32", "few")])
 def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
-    """Long vectors on the matrix-core path: the accept set is guessed from the first 2^22
-    elements and the Gram pass writes the mean of the guess. Here some gradients agree with the
-    seed on that prefix and oppose it on the rest, so the guess is wrong and the stand-alone
-    mean must take over; a second batch has a consistent prefix (guess right). With the "few"
+    """Long vectors on the matrix-core path: the accept set is guessed from a sample of 2^22
+    elements (256 evenly spaced runs of 2^14, as the header documents) and the Gram pass writes
+    the mean of the guess. Here some gradients agree with the seed on the sampled elements and
+    oppose it on the rest, so the guess is wrong and the stand-alone mean must take over; a
+    second batch is twisted on a prefix instead and a third not at all (guess right). With the "few"
     pattern only one gradient in five agrees with the seed: below a break-even accept count the
     Gram pass leaves the mean to the stand-alone kernel even when the guess is right."""
     P = (1 << 26) + 12_345
     gen = torch.Generator(device="cuda").manual_seed(100 + N)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     c = torch.randn(P, generator=gen, device="cuda")
-    flip = torch.ones(P, device="cuda"); flip[: 1 << 22] = -1.0
+    run, stride = 1 << 14, (P // 256) // (1 << 14) * (1 << 14)
+    sampled = (torch.arange(256, device="cuda")[:, None] * stride + torch.arange(run, device="cuda")[None, :]).reshape(-1)
+    flip = torch.ones(P, device="cuda"); flip[sampled] = -1.0
+    flip_prefix = torch.ones(P, device="cuda"); flip_prefix[: 1 << 22] = -1.0
     signs = ([1, 1, -1, 1, -1] if pattern == "mixed" else [1, -1, -1, -1, -1]) * (N // 5)
-    for twist in (True, False):
+    # twist "sample": on the sampled elements; "prefix": on the first 2^22 elements instead (one
+    # atypical layer at the front: the spread-out sample must not be misled by it)
+    for twist in ("sample", "prefix", None):
         grads = []
         for i in range(N):
             z = torch.randn(P, generator=gen, device="cuda")
             g = signs[i] * 0.4 * c + 0.9 * z
             if twist and i in (1, 2, N - 1):   # (for N = 5: gradients 1, 2 and 4)
-                g = g + (flip - 1.0) * signs[i] * 0.4 * c      # opposite relation to c on the prefix only
+                f = flip if twist == "sample" else flip_prefix
+                g = g + (f - 1.0) * signs[i] * 0.4 * c      # opposite relation to c on those elements only
             grads.append(g.to(tdt))
             del z, g
+        gaf.gaf_set_schedule(ctx, ctx.schedule_name)      # also forgets earlier guesses
+        gaf.gaf_profile_begin(ctx)
         res = gaf.gaf_aggregate(ctx, grads, 0.95)
+        launches = gaf.gaf_profile_end(ctx)
         torch.cuda.synchronize()
         ref = _oracle_sequential_from_device(oracle, grads, 0.95)
         assert np.all(np.abs(ref[2][1:] - np.float32(0.95)) >= MARGIN)
         check_against_oracle(res, ref, dtype)
         if ctx.schedule_name == "auto":
+            # Did the device sample where the header says? With the twist on exactly those elements
+            # the guess must be wrong and the stand-alone mean must do its work (>= 150 us at this
+            # size); without it, and with enough accepted for the fused write, it returns at once
+            # (a few us).
+            mean_ms = [ms for name, ms in launches if name == "mean"]
+            assert len(mean_ms) == 1 and any(name == "gram_sample" for name, _ in launches)
+            rec = gaf.gaf_fused_mean_record(ctx)
+            if twist == "sample" or pattern == "few":
+                assert mean_ms[0] > 0.05, launches
+                assert rec["valid"] == 0
+            else:
+                assert mean_ms[0] < 0.05, launches
+                assert rec == {"write": 1, "valid": 1, "backoff": 0, "penalty": 1}
+            if twist == "sample" and pattern == "mixed":
+                assert rec == {"write": 1, "valid": 0, "backoff": 1, "penalty": 2}
             # whether the guess was right or wrong, the result equals the two-pass schedule's bit for bit
             gaf.gaf_set_schedule(ctx, "gram")
             two_pass = gaf.gaf_aggregate(ctx, grads, 0.95)
@@ -423,11 +448,49 @@ def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
             for x, y in zip(res, two_pass):
                 assert torch.equal(x, y)
             del two_pass
-        if twist:
-            # the prefix alone would have decided differently for the twisted gradients
-            pre = oracle.aggregate([wl.to_host_array(g[: 1 << 22]) for g in grads], np.float32(0.95))
+        if twist == "sample":
+            # the sample alone would have decided differently for the twisted gradients
+            pre = oracle.aggregate([wl.to_host_array(g[sampled]) for g in grads], np.float32(0.95))
             assert pre[1].tolist() != ref[1].tolist()
         del grads, res
+
+
+def test_fused_mean_backs_off_after_wrong_guesses(ctx):
+    """The context's record of guesses: a written guess that proves wrong stops the writing for
+    `penalty` calls and doubles the penalty, a right one halves it. Batch A is built so that the
+    sample misleads (see the test above), batch B so that it does not; every call's result must
+    equal the two-pass schedule's bit for bit whatever the record says."""
+    if ctx.schedule_name != "auto":
+        pytest.skip("the fused mean belongs to the AUTO schedule")
+    P, N = (1 << 26) + 64, 10
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    c = torch.randn(P, generator=gen, device="cuda")
+    stride = (P // 256) // (1 << 14) * (1 << 14)
+    sampled = (torch.arange(256, device="cuda")[:, None] * stride + torch.arange(1 << 14, device="cuda")[None, :]).reshape(-1)
+    flip = torch.ones(P, device="cuda"); flip[sampled] = -1.0
+    signs = [1, 1, -1, 1, -1] * 2
+    batches = {}
+    for name in "AB":
+        grads = []
+        for i in range(N):
+            g = signs[i] * 0.4 * c + 0.9 * torch.randn(P, generator=gen, device="cuda")
+            if name == "A" and i in (1, 2, N - 1):
+                g = g + (flip - 1.0) * signs[i] * 0.4 * c
+            grads.append(g.to(torch.bfloat16)); del g
+        gaf.gaf_set_schedule(ctx, "gram")
+        expect = [t.clone() for t in gaf.gaf_aggregate(ctx, grads, 0.95)]
+        batches[name] = (grads, expect)
+    gaf.gaf_set_schedule(ctx, "auto")
+    assert gaf.gaf_fused_mean_record(ctx) == {"write": 0, "valid": 0, "backoff": 0, "penalty": 1}
+    script = [("A", 1, 0, 1, 2), ("B", 0, 0, 0, 2), ("B", 1, 1, 0, 1), ("A", 1, 0, 1, 2), ("A", 0, 0, 0, 2),
+              ("A", 1, 0, 2, 4), ("B", 0, 0, 1, 4), ("B", 0, 0, 0, 4), ("B", 1, 1, 0, 2), ("B", 1, 1, 0, 1)]
+    for step, (name, write, valid, backoff, penalty) in enumerate(script):
+        grads, expect = batches[name]
+        res = gaf.gaf_aggregate(ctx, grads, 0.95)
+        rec = gaf.gaf_fused_mean_record(ctx)
+        assert rec == {"write": write, "valid": valid, "backoff": backoff, "penalty": penalty}, (step, rec)
+        for x, y in zip(res, expect):
+            assert torch.equal(x, y), step
 
 
 @pytest.mark.timeout(600)
