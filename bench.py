@@ -283,6 +283,38 @@ def main():
         gaf.gaf_set_schedule(ctx, args.schedule)
         state["schedule"] = args.schedule
 
+    # ---- what this GPU's memory system delivers to the simplest kernels of the library, measured
+    # now: a read-only pass (inner products of two binary32 vectors of 2^28 elements: 2 GiB read)
+    # and a plain copy (a single-gradient batch: 1 GiB read, 1 GiB written). The dominant kernel's
+    # rate is also reported as a fraction of whichever of the two matches its read/write mix.
+    ceilings = None
+    try:
+        E = 1 << 28
+        a_c = torch.ones(E, dtype=torch.float32, device="cuda")
+        b_c = torch.full((E,), 0.5, dtype=torch.float32, device="cuda")
+        cal = gaf.gaf_create(max_P=E, max_N=2)
+        o_c = gaf.gaf_aggregate(cal, [a_c], 1.0)
+        d_c = gaf.gaf_pairwise(cal, [a_c, b_c])
+        torch.cuda.synchronize()
+        gaf.gaf_profile_begin(cal, 256)
+        for _ in range(5):
+            gaf.gaf_aggregate(cal, [a_c], 1.0, *o_c)
+            gaf.gaf_pairwise(cal, [a_c, b_c], d_c)
+        kt = {}
+        for name, ms in gaf.gaf_profile_end(cal, 256):
+            kt.setdefault(name, []).append(ms)
+        ceilings = {"read_only": 2 * 4 * E / (min(kt["gram"]) * 1e-3) / 1e9,
+                    "copy": 2 * 4 * E / (min(kt["update"]) * 1e-3) / 1e9, "unit": "GB/s",
+                    "how": "best of 5 launches each: inner products of two 2^28-element binary32 vectors "
+                           "(read-only), single-gradient batch of one such vector (copy)"}
+        writes = (dom == "gram" and fused) or dom == "mean" or (dom == "reduce" and w.mode != "step")
+        roof["frac_of_measured_ceiling"] = (roof["achieved"] / ceilings["copy" if writes else "read_only"]
+                                            if roof["bound"] == "hbm" else None)
+        gaf.gaf_destroy(cal)
+        del a_c, b_c, o_c, d_c
+    except (torch.OutOfMemoryError, KeyError) as e:      # the workload left no room, or a kernel was renamed
+        ceilings = {"error": repr(e)}
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     cpu = None
     if args.cpu_seconds > 0:
@@ -343,6 +375,7 @@ def main():
                    "algorithmic_bytes_per_step": step_bytes,
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,
+        "measured_ceilings": ceilings,
         "cpu_baseline": cpu,
         "other_schedules": other,
         "kernel_ms": {k: sum(v) / len(v) for k, v in per_kernel.items()},
