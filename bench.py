@@ -8,6 +8,12 @@ micro-gradients already resident in HBM: a full gaf_aggregate (batch
 workloads), N gaf_step calls (streaming), or gaf_aggregate_with_matrix
 (diagnostic: distance matrix plus filter). Prints ONE JSON line.
 
+Vectors of 2^21 .. 2^26 elements: the batch call guesses each call's accept set from the previous
+call's. Timing one batch over and over would make every guess right, which no training run
+does; so for those sizes the steps cycle through several independently drawn batches
+(--batches, default 4), and the run with one repeated batch is reported separately under
+other_schedules as the all-guesses-right bound.
+
 value = effective HBM GB/s = (bytes the method itself must move) / time:
     per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted (write it),
     once per batch        s*P + 4*P for the seed,
@@ -63,10 +69,17 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--P", type=int, default=None, help="override the vector length")
     ap.add_argument("--N", type=int, default=None, help="override the number of micro-gradients")
+    ap.add_argument("--batches", type=int, default=0,
+                    help="independently drawn batches (seeds seed, seed+1, ...) the steps cycle through; "
+                         "0 = 4 where the library carries guesses from call to call, else 1")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
                     help="before anything else run one plain copy of ELEMS binary32 elements through "
                          "the library (a single-gradient batch: reads 4*ELEMS bytes, writes 4*ELEMS): "
                          "the known-size dispatch that profiler byte counters are scaled by")
+    ap.add_argument("--only-profile-loop", action="store_true",
+                    help="for runs under a profiler: skip the timed loop, the other schedules, the ceilings "
+                         "and the CPU baseline, so that the last --steps launches of every kernel are exactly "
+                         "the ones the per-kernel figures (roofline) are computed from")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
     args = ap.parse_args()
@@ -109,6 +122,12 @@ def main():
     fused = schedule_used == "gram_first" and args.schedule == "auto" and P >= (1 << 26)
     if fused:
         schedule_used = "gram_first_fused_mean"
+    # shorter vectors: the guess is the previous call's accept set
+    carried = schedule_used == "gram_first" and args.schedule == "auto" and (1 << 21) <= P < (1 << 26)
+    B = args.batches if args.batches > 0 else (4 if carried and not args.graph else 1)
+    batches = [grads] + [wl.generate(args.workload, args.seed + j, P=args.P, N=args.N, device="cuda")[1]
+                         for j in range(1, B)]
+    torch.cuda.synchronize()
 
     out = torch.empty(P, dtype=torch.float32, device="cuda")
     mask = torch.empty(N, dtype=torch.uint8, device="cuda")
@@ -119,7 +138,8 @@ def main():
 
     state = {"schedule": args.schedule}
 
-    def step():
+    def step(k=0):
+        grads = batches[k % B]
         if w.mode == "step":
             count.zero_()
             for i, g in enumerate(grads):
@@ -133,8 +153,16 @@ def main():
                 gaf.gaf_pairwise(ctx, grads, D=D)
             gaf.gaf_aggregate(ctx, grads, w.tau, out, mask, dist, count)
 
-    for _ in range(args.warmup):
-        step()
+    # every batch once: its accept mask (for the bytes the method must move) and a warm-up
+    masks, dists, counts = [], [], []
+    for b in range(B):
+        step(b)
+        torch.cuda.synchronize()
+        masks.append(mask.cpu().numpy().tolist())
+        dists.append(dist.cpu().numpy().tolist())
+        counts.append(int(count.item()))
+    for k in range(args.warmup):
+        step(k)
     torch.cuda.synchronize()
     run_step = step
     if args.graph:
@@ -147,30 +175,34 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
-        run_step = graph.replay
+        run_step = lambda k=0: graph.replay()
         run_step()
         torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        run_step()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_s = time.perf_counter() - t0
-    ms_per_step = 1e3 * wall_s / args.steps
-    ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
+    mask_h, dist_h, c_h = masks[0], dists[0], counts[0]
+    step_bytes = sum(bmin_bytes(w, masks[k % B]) for k in range(args.steps)) / args.steps
+    ms_per_step = ms_per_step_events = value = None
+    if not args.only_profile_loop:
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for k in range(args.steps):
+            run_step(k)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t0
+        ms_per_step = 1e3 * wall_s / args.steps
+        ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
+        value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    mask_h = mask.cpu().numpy().tolist()
-    dist_h = dist.cpu().numpy().tolist()
-    c_h = int(count.item())
-    step_bytes = bmin_bytes(w, mask_h)
-    value = step_bytes / (ms_per_step * 1e-3) / 1e9
-
-    # ---- per-kernel durations over the same steps, HIP events on the launch stream ----
+    # ---- per-kernel durations over the same steps, HIP events on the launch stream; where the
+    # Gram pass may write the mean of a guess, the library's record says after each step whether
+    # it did and whether the guess was right (reading it waits for the device: not in the timed loop)
     gaf.gaf_profile_begin(ctx, 65536)
-    for _ in range(args.steps):
-        step()
+    records = []
+    for k in range(args.steps):
+        step(k)
+        if fused or carried:
+            records.append(gaf.gaf_fused_mean_record(ctx))
     times = gaf.gaf_profile_end(ctx, 65536)
     per_kernel = {}
     for name, ms in times:
@@ -188,7 +220,10 @@ def main():
         # one launch reads every gradient once
         dur = per_kernel["gram"]
         avg_ms = sum(dur) / len(dur)
-        alg_bytes = float(N * s * P) + (4.0 * P if fused else 0.0)   # fused: the result is written too
+        alg_bytes = float(N * s * P)
+        if records:                 # launches that also wrote the mean of their guess
+            assert len(dur) == len(records)
+            alg_bytes += 4.0 * P * sum(r["write"] for r in records) / len(records)
         r = hbm_roof(alg_bytes, avg_ms)
         if N <= 8:
             # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
@@ -216,24 +251,29 @@ def main():
             else:
                 r["mfma_frac"] = mfma_frac
         roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
-    if "mean" in per_kernel and not fused:     # fused: the stand-alone mean only runs after a wrong guess
+    if "mean" in per_kernel:
+        # accepted gradients read once, result written once; a launch that finds the result in
+        # place (right guess) returns at once and is left out
         dur = per_kernel["mean"]
-        avg_ms = sum(dur) / len(dur)
-        alg_bytes = float(c_h * s * P + 4 * P)      # accepted gradients read once, result written once
-        roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
+        assert len(dur) == args.steps
+        live = [k for k in range(args.steps) if not (records and records[k]["valid"])]
+        if live:
+            avg_ms = sum(dur[k] for k in live) / len(live)
+            alg_bytes = sum(float(counts[k % B] * s * P + 4 * P) for k in live) / len(live)
+            roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur[k] for k in live))
     if "reduce" in per_kernel:
         # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
         # gradient i - 1 if that one was accepted; a streaming reduce never stores.
         if w.mode == "step":
             # the launch for the seed returns at once (nothing to compare with): not counted
-            per_launch = [None] + [(4 + s) * P] * (N - 1)
+            per_launch = ([None] + [(4 + s) * P] * (N - 1)) * args.steps
         else:
-            per_launch = [(4 + s) * P + (4 * P if mask_h[i - 1] else 0) for i in range(2, N)]
+            per_launch = [(4 + s) * P + (4 * P if masks[k % B][i - 1] else 0)
+                          for k in range(args.steps) for i in range(2, N)]
         dur = per_kernel["reduce"]
-        n_per_step = len(per_launch)
-        assert len(dur) == n_per_step * args.steps, (len(dur), n_per_step, args.steps)
-        dur = [d for k, d in enumerate(dur) if per_launch[k % n_per_step] is not None]
-        alg = sum(b for b in per_launch if b is not None) * args.steps
+        assert len(dur) == len(per_launch), (len(dur), len(per_launch))
+        dur = [d for k, d in enumerate(dur) if per_launch[k] is not None]
+        alg = sum(b for b in per_launch if b is not None)
         avg_ms = sum(dur) / max(1, len(dur))
         alg_bytes = alg / max(1, len(dur))
         roofs["reduce"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
@@ -250,31 +290,43 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as fh:
             tj = json.load(fh)
+        # measured HBM bytes per launch of this kernel in the profiler run, as a ratio to the
+        # algorithmic bytes per launch of that same run; scaled to this run's launches
         ent = tj.get("%s/%s/%s" % (w.name, schedule_used, dom))
         if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
-            roof["traffic"] = ent["hbm_bytes_per_launch"]
+            roof["traffic"] = ent["hbm_bytes_over_algorithmic"] * alg_bytes
+            roof["traffic_over_algorithmic"] = ent["hbm_bytes_over_algorithmic"]
 
     # ---- the other schedules of the batch call, for comparison (fewer steps) ----
     other = None
-    if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64:
+    if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64 and not args.only_profile_loop:
         other = []
-        for sched in (["gram"] if fused else []) + ["sequential"]:
+        # (label, schedule); all on the first batch, repeated
+        runs = [("gram_two_pass", "gram")] if fused or carried else []
+        if carried and not args.graph:
+            runs.append(("gram_first_one_batch_repeated_every_guess_right", "auto"))
+        runs.append(("sequential", "sequential"))
+        for label, sched in runs:
             gaf.gaf_set_schedule(ctx, sched)
             state["schedule"] = sched
-            k = max(3, args.steps // 4)
+            # short steps: as many as the main loop, or the host's launch overhead shows
+            k = args.steps if ms_per_step < 1.0 else max(3, args.steps // 4)
+            step()
             step()
             torch.cuda.synchronize()
-            gaf.gaf_profile_begin(ctx, 65536)
             t0 = time.perf_counter()
             for _ in range(k):
                 step()
             torch.cuda.synchronize()
             ms_o = 1e3 * (time.perf_counter() - t0) / k
+            gaf.gaf_profile_begin(ctx, 65536)      # per-kernel times in a loop of their own: the event
+            for _ in range(k):                     # brackets cost time between launches
+                step()
             kt = {}
             for name, ms in gaf.gaf_profile_end(ctx, 65536):
                 kt.setdefault(name, []).append(ms)
-            entry = {"schedule": "gram_two_pass" if sched == "gram" else sched, "steps": k,
-                     "ms_per_step": ms_o, "value": step_bytes / (ms_o * 1e-3) / 1e9,
+            entry = {"schedule": label, "steps": k,
+                     "ms_per_step": ms_o, "value": bmin_bytes(w, masks[0]) / (ms_o * 1e-3) / 1e9,
                      "kernel_ms": {n: sum(v) / len(v) for n, v in kt.items()}}
             if sched == "gram" and "gram" in kt:
                 g_ms = sum(kt["gram"]) / len(kt["gram"])
@@ -288,36 +340,38 @@ def main():
     # and a plain copy (a single-gradient batch: 1 GiB read, 1 GiB written). The dominant kernel's
     # rate is also reported as a fraction of whichever of the two matches its read/write mix.
     ceilings = None
-    try:
-        E = 1 << 28
-        a_c = torch.ones(E, dtype=torch.float32, device="cuda")
-        b_c = torch.full((E,), 0.5, dtype=torch.float32, device="cuda")
-        cal = gaf.gaf_create(max_P=E, max_N=2)
-        o_c = gaf.gaf_aggregate(cal, [a_c], 1.0)
-        d_c = gaf.gaf_pairwise(cal, [a_c, b_c])
-        torch.cuda.synchronize()
-        gaf.gaf_profile_begin(cal, 256)
-        for _ in range(5):
-            gaf.gaf_aggregate(cal, [a_c], 1.0, *o_c)
-            gaf.gaf_pairwise(cal, [a_c, b_c], d_c)
-        kt = {}
-        for name, ms in gaf.gaf_profile_end(cal, 256):
-            kt.setdefault(name, []).append(ms)
-        ceilings = {"read_only": 2 * 4 * E / (min(kt["gram"]) * 1e-3) / 1e9,
-                    "copy": 2 * 4 * E / (min(kt["update"]) * 1e-3) / 1e9, "unit": "GB/s",
-                    "how": "best of 5 launches each: inner products of two 2^28-element binary32 vectors "
-                           "(read-only), single-gradient batch of one such vector (copy)"}
-        writes = (dom == "gram" and fused) or dom == "mean" or (dom == "reduce" and w.mode != "step")
-        roof["frac_of_measured_ceiling"] = (roof["achieved"] / ceilings["copy" if writes else "read_only"]
-                                            if roof["bound"] == "hbm" else None)
-        gaf.gaf_destroy(cal)
-        del a_c, b_c, o_c, d_c
-    except (torch.OutOfMemoryError, KeyError) as e:      # the workload left no room, or a kernel was renamed
-        ceilings = {"error": repr(e)}
+    if not args.only_profile_loop:
+        try:
+            E = 1 << 28
+            a_c = torch.ones(E, dtype=torch.float32, device="cuda")
+            b_c = torch.full((E,), 0.5, dtype=torch.float32, device="cuda")
+            cal = gaf.gaf_create(max_P=E, max_N=2)
+            o_c = gaf.gaf_aggregate(cal, [a_c], 1.0)
+            d_c = gaf.gaf_pairwise(cal, [a_c, b_c])
+            torch.cuda.synchronize()
+            gaf.gaf_profile_begin(cal, 256)
+            for _ in range(5):
+                gaf.gaf_aggregate(cal, [a_c], 1.0, *o_c)
+                gaf.gaf_pairwise(cal, [a_c, b_c], d_c)
+            kt = {}
+            for name, ms in gaf.gaf_profile_end(cal, 256):
+                kt.setdefault(name, []).append(ms)
+            ceilings = {"read_only": 2 * 4 * E / (min(kt["gram"]) * 1e-3) / 1e9,
+                        "copy": 2 * 4 * E / (min(kt["update"]) * 1e-3) / 1e9, "unit": "GB/s",
+                        "how": "best of 5 launches each: inner products of two 2^28-element binary32 vectors "
+                               "(read-only), single-gradient batch of one such vector (copy)"}
+            writes = ((dom == "gram" and any(r["write"] for r in records)) or dom == "mean" or
+                      (dom == "reduce" and w.mode != "step"))
+            roof["frac_of_measured_ceiling"] = (roof["achieved"] / ceilings["copy" if writes else "read_only"]
+                                                if roof["bound"] == "hbm" else None)
+            gaf.gaf_destroy(cal)
+            del a_c, b_c, o_c, d_c
+        except (torch.OutOfMemoryError, KeyError) as e:      # the workload left no room, or a kernel was renamed
+            ceilings = {"error": repr(e)}
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
     cpu = None
-    if args.cpu_seconds > 0:
+    if args.cpu_seconds > 0 and not args.only_profile_loop:
         from oracle import gaf_oracle
         cores = gaf_oracle.num_threads()
         # sample: all N micro-gradients, the first Ps coordinates of each
@@ -356,8 +410,8 @@ def main():
         "metric": "gaf_filter_average_effective_hbm_gbps",
         "value": value,
         "unit": "GB/s",
-        "pct_of_hbm_peak": 100.0 * value / PEAK_HBM_GBPS,
-        "micro_gradients_per_s": N / (ms_per_step * 1e-3),
+        "pct_of_hbm_peak": None if value is None else 100.0 * value / PEAK_HBM_GBPS,
+        "micro_gradients_per_s": None if ms_per_step is None else N / (ms_per_step * 1e-3),
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -372,6 +426,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau,
                    "mode": w.mode, "schedule": schedule_used, "hip_graph": bool(args.graph), "seed": args.seed, "accepted": c_h,
+                   "batches": B, "accepted_per_batch": counts,
+                   "guesses": ({"source": "sample of this call's gradients" if fused else "previous call's accept set",
+                                "mean_written_by_gram_pass": sum(r["write"] for r in records),
+                                "right": sum(r["valid"] for r in records), "steps": len(records)}
+                               if records else None),
                    "algorithmic_bytes_per_step": step_bytes,
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,

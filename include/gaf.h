@@ -143,7 +143,11 @@ gaf_status gaf_aggregate(gaf_ctx *ctx, const void *const *grads, int N, size_t P
  *               the guess names only a few gradients (fewer than a break-even
  *               count between 2 and 10 that depends on dtype and N) the Gram pass
  *               stays read-only and the separate mean pass, cheap for so few
- *               gradients, does the work. A context also keeps a record of its
+ *               gradients, does the work. Shorter vectors (2^21 <= P < 2^26),
+ *               where a sample would cost too large a share, use the accept set
+ *               of the context's previous call with the same N as the guess
+ *               (agreement drifts slowly over training; with two micro-batches
+ *               the guess is simply "as last time"). A context also keeps a record of its
  *               guesses on the device: a written guess that proves wrong stops
  *               the writing for the next `penalty` calls (1 at first, doubling
  *               per miss up to 64, halving per hit), so callers whose distances

@@ -60,18 +60,19 @@ __device__ __forceinline__ int run_filter(const double *gram, int N, int seed, f
 }
 
 // What a filter launch does with the context's Prediction.
-enum : int { kSpecNone = 0, kSpecGuess = 1, kSpecVerify = 2 };
+enum : int { kSpecNone = 0, kSpecGuess = 1, kSpecVerify = 2, kSpecVerifyCarried = 3 };
 
 // kSpecGuess (run on the inner products of a sample; accepted_list = pred->list): records the
 // guessed accept set and decides whether this call's Gram pass writes its mean -- only if the
 // guess names at least min_count gradients (below that the stand-alone mean is cheaper than
 // mixing writes into the reading pass) and no backoff from an earlier wrong guess is running.
-// kSpecVerify (run on the full inner products): compares the guess with the accept set just
-// computed, tells the mean kernel whether the result is already in place, and keeps the record:
-// a written guess that was wrong stops writing for `penalty` calls and doubles the penalty, a
-// right one halves it; a call that did not write counts the backoff down. All on the device, so
-// a caller whose gradients sit close to the threshold stops paying for wrong guesses without
-// ever synchronising.
+// kSpecVerify / kSpecVerifyCarried (run on the full inner products): compares the guess with the
+// accept set just computed, tells the mean kernel whether the result is already in place, and
+// keeps the record: a written guess that was wrong stops writing for `penalty` calls and doubles
+// the penalty, a right one halves it; a call that did not write counts the backoff down. The
+// carried form then stores the accept set just computed as the next call's guess. All on the
+// device, so a caller whose gradients sit close to the threshold stops paying for wrong guesses
+// without ever synchronising.
 __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
                                                     uint8_t *mask, float *cos_dist, int32_t *count,
                                                     int32_t *accepted_list, int spec = kSpecNone,
@@ -88,13 +89,16 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
         if (threadIdx.x == 0) {
             pred->write = (c >= min_count && pred->backoff == 0) ? 1 : 0;
             pred->valid = 0;
+            pred->n = N;
         }
-    } else if (spec == kSpecVerify) {
+    } else if (spec == kSpecVerify || spec == kSpecVerifyCarried) {
         if (threadIdx.x == 0) {      // the thread that wrote accepted_list above
+            const bool carried = spec == kSpecVerifyCarried;
+            const bool wrote = carried ? carried_guess_writes(pred, N, min_count) : pred->write != 0;
             bool same = pred->count == c;
             for (int k = 0; same && k < c; ++k) same = pred->list[k] == accepted_list[k];
             int penalty = pred->penalty < 1 ? 1 : pred->penalty;
-            if (pred->write) {
+            if (wrote) {
                 if (same) {
                     penalty = penalty > 1 ? penalty / 2 : 1;
                 } else {
@@ -105,7 +109,13 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
                 pred->backoff -= 1;
             }
             pred->penalty = penalty;
-            pred->valid = (pred->write && same) ? 1 : 0;
+            pred->write = wrote ? 1 : 0;
+            pred->valid = (wrote && same) ? 1 : 0;
+            if (carried) {
+                pred->n = N;
+                pred->count = c;
+                for (int k = 0; k < c; ++k) pred->list[k] = accepted_list[k];
+            }
         }
     }
 }
@@ -114,6 +124,7 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
 __global__ void prediction_reset_kernel(Prediction *pred)
 {
     pred->count = 0;
+    pred->n = 0;
     pred->write = 0;
     pred->valid = 0;
     pred->backoff = 0;
@@ -176,6 +187,7 @@ struct SmallGramArgs {
     double *partials;     // [pairs][kMaxBlocks]
     const Prediction *pred;   // kMean only
     float *mean_out;
+    int carry_n, min_count;   // kMean only: see GramArgs
     size_t chunk_stride;      // non-zero: sampling launch, see gram_small_range
 };
 
@@ -195,7 +207,7 @@ template <typename T, int N, bool kStream, bool kMean = false>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
                                                  size_t first, size_t stride, double *out, size_t out_stride,
                                                  const Prediction *pred = nullptr, float *mean_out = nullptr,
-                                                 size_t chunk_stride = 0)
+                                                 size_t chunk_stride = 0, int carry_n = 0, int min_count = 0)
 {
     constexpr int NP = N * (N + 1) / 2;
     constexpr int U = small_gram_unroll(N);
@@ -215,8 +227,9 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     float inv_c = 0.f;
 #pragma unroll
     for (int i = 0; i < N; ++i) take[i] = false;
-    const bool write_mean = kMean && pred->write != 0;
-    if (kMean) {
+    const bool write_mean =
+        kMean && (carry_n ? carried_guess_writes(pred, carry_n, min_count) : pred->write != 0);
+    if (kMean && write_mean) {
         const int c = pred->count;
         inv_c = 1.0f / (float)c;
         for (int k = 0; k < c; ++k) {
@@ -276,7 +289,9 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
                             m.w += v[u][i].w;
                         }
                     const f32x4_t o = {m.x * inv_c, m.y * inv_c, m.z * inv_c, m.w * inv_c};
-                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t *>(mean_out + base + size_t(u) * kBlock * 4));
+                    f32x4_t *dst = reinterpret_cast<f32x4_t *>(mean_out + base + size_t(u) * kBlock * 4);
+                    if (kStream) __builtin_nontemporal_store(o, dst);
+                    else *dst = o;
                 }
             }
         } else {
@@ -319,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
 {
     // partials laid out [pair][kMaxBlocks]
     gram_small_range<T, N, kStream, kMean>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x,
-                                           kMaxBlocks, a.pred, a.mean_out, a.chunk_stride);
+                                           kMaxBlocks, a.pred, a.mean_out, a.chunk_stride, a.carry_n, a.min_count);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner

@@ -71,19 +71,33 @@ struct TileList {
 // 3-4 KB of loads in flight per wavefront whatever the row count.
 __host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 8 : ng == 2 ? 4 : 2; }
 
-// An accept set guessed before the full inner products are known (from a sample
-// of the vectors): which gradients Algorithm 1 will probably accept, in visiting order,
-// and what is done with the guess. Lives in device memory for the context's lifetime:
-// the last two fields carry the record of earlier guesses from call to call.
+// An accept set guessed before the full inner products are known: which gradients
+// Algorithm 1 will probably accept, in visiting order, and what is done with the guess.
+// Two sources of guesses: for long vectors a filter run on a sample of the vectors
+// (it also decides `write`); for shorter ones, where a sample would cost too large a share,
+// the accept set of the previous call with the same N (agreement rates drift slowly over
+// training; with the two micro-batches of the paper's experiments the guess is simply
+// "as last time"). Lives in device memory for the context's lifetime: the fields from `n` on
+// carry the record from call to call.
 struct Prediction {
     int32_t count;
     int32_t list[kGramRows];
-    int32_t write;     // this call's Gram pass writes the mean of the guess (set by the sample's filter)
+    int32_t write;     // this call's Gram pass writes the mean of the guess
     int32_t valid;     // ... and the guess was right: the result is in place (set by the full filter)
+    int32_t n;         // batch size the guess belongs to
     int32_t backoff;   // calls left during which no guess is written, after a wrong one
     int32_t penalty;   // backoff imposed by the next wrong guess: doubles per miss up to kSpecMaxPenalty,
                        // halves per hit; 0 = never used, treated as 1
 };
+
+// Guess carried over from the previous call (carry_n = this call's N): is it usable, and does
+// this call's Gram pass therefore write its mean? Evaluated identically by every workgroup of
+// the Gram pass and, afterwards, by the filter that verifies the guess; the record is not
+// modified in between.
+__device__ __forceinline__ bool carried_guess_writes(const Prediction *p, int carry_n, int min_count)
+{
+    return p->n == carry_n && p->count >= min_count && p->count <= carry_n && p->backoff == 0;
+}
 constexpr int kSpecMaxPenalty = 64;
 
 struct GramArgs {
@@ -94,7 +108,9 @@ struct GramArgs {
     // kMean only: the mean of the predicted accept set is formed from the staged data and written here
     const Prediction *pred;
     float *out;
-    // kMean launches write the mean only if pred->write says so.
+    // kMean launches write the mean only if pred->write says so (carry_n == 0: guess from a sample)
+    // or if carried_guess_writes(pred, carry_n, min_count) (guess carried over from the last call).
+    int carry_n, min_count;
     // Sampling launches read runs of 2^chunk_shift stages, run r starting at element r * chunk_stride;
     // an ordinary launch has chunk_shift = 62 (one run that never ends) and chunk_stride = 0.
     int chunk_shift;
@@ -203,7 +219,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     bool write_mean = false;
     if (kMean) {
         c_pred = a.pred->count;
-        write_mean = a.pred->write != 0;
+        write_mean = a.carry_n ? carried_guess_writes(a.pred, a.carry_n, a.min_count) : a.pred->write != 0;
+        if (!write_mean) c_pred = 0;
         if (int(threadIdx.x) < c_pred) pred_rows[threadIdx.x] = a.pred->list[threadIdx.x];
     }
     __syncthreads();

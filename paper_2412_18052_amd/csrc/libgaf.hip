@@ -220,6 +220,15 @@ constexpr int fused_min_count(int groups)
     constexpr int f32_min[5] = {2, 4, 7, 7, 7};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
+// The same for a batch of N gradients. A guess carried over from the previous call is used on
+// shorter vectors, where the small-batch kernel gains from writing even a one-gradient "mean"
+// (the stand-alone pass would cost a launch and a second read of that gradient).
+template <typename T>
+int spec_min_count(int N, bool carried)
+{
+    if (N <= kSmallMaxN) return carried ? 1 : fused_min_count<T>(0);
+    return fused_min_count<T>((N + 15) / 16);
+}
 
 // Enqueues the Gram kernel for up to four 16-row groups (global group indices in
 // `groups`, -1 = absent) and the ordered combine of its per-workgroup tiles into
@@ -230,7 +239,7 @@ constexpr int fused_min_count(int groups)
 template <typename T, int NG, int kMode>
 gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, const int (&groups)[4],
                        hipStream_t s, gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr,
-                       size_t chunk_stride = 0)
+                       size_t chunk_stride = 0, int carry_n = 0)
 {
     constexpr size_t kStagesPerChunk = kSampleChunk / (size_t(256) * gram_stage_m(NG) / sizeof(T));
     static_assert(kStagesPerChunk >= 1 && (kStagesPerChunk & (kStagesPerChunk - 1)) == 0, "power of two");
@@ -249,6 +258,8 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     g.ws = ctx->gram_ws;
     g.pred = ctx->pred;
     g.out = mean_out;
+    g.carry_n = carry_n;
+    g.min_count = spec_min_count<T>(N, carry_n != 0);
     g.chunk_shift = 62;
     if (chunk_stride)
         for (g.chunk_shift = 0; (size_t(1) << g.chunk_shift) < kStagesPerChunk;) ++g.chunk_shift;
@@ -283,7 +294,8 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
 // `mean_out` (N <= 64 only): see gram_launch.
 template <typename T>
 gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
-                          gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0)
+                          gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0,
+                          int carry_n = 0)
 {
     const int ng = (N + 15) / 16;
     for (int g0 = 0; g0 < ng; g0 += 4) {
@@ -291,10 +303,10 @@ gaf_status gram_all_pairs(gaf_ctx *ctx, const void *const *grads, int N, size_t 
         const int groups[4] = {g0, n > 1 ? g0 + 1 : -1, n > 2 ? g0 + 2 : -1, n > 3 ? g0 + 3 : -1};
         gaf_status rc = GAF_OK;
         switch (n) {
-        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
-        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
-        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
-        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride); break;
+        case 1: rc = gram_launch<T, 1, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride, carry_n); break;
+        case 2: rc = gram_launch<T, 2, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride, carry_n); break;
+        case 3: rc = gram_launch<T, 3, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride, carry_n); break;
+        default: rc = gram_launch<T, 4, kFull>(ctx, grads, N, P, groups, s, id, mean_out, chunk_stride, carry_n); break;
         }
         if (rc != GAF_OK) return rc;
     }
@@ -316,7 +328,7 @@ template <typename T, bool kStream, int N>
 gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 {
     if (g.mean_out)
-        gram_small_kernel<T, N, true, true><<<nb, kBlock, 0, s>>>(g);   // long vectors only: streaming loads
+        gram_small_kernel<T, N, kStream, true><<<nb, kBlock, 0, s>>>(g);
     else
         gram_small_kernel<T, N, kStream><<<nb, kBlock, 0, s>>>(g);
     return launched();
@@ -325,7 +337,8 @@ gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 // With `mean_out` the launch also writes the mean of ctx->pred's accept set there.
 template <typename T, bool kStream>
 gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
-                      gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0)
+                      gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0,
+                      int carry_n = 0)
 {
     if (chunk_stride && (mean_out || P % kSampleChunk)) return GAF_EINVAL;
     SmallGramArgs g{};
@@ -335,6 +348,8 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
     g.pred = ctx->pred;
     g.mean_out = mean_out;
     g.chunk_stride = chunk_stride;
+    g.carry_n = carry_n;
+    g.min_count = spec_min_count<T>(N, carry_n != 0);
     // at most two workgroups per CU: few partial sums to combine afterwards, and the widest
     // variant (N = 8) does not fit more anyway
     const int nb = pass_blocks(P) < kSmallBlocks ? pass_blocks(P) : kSmallBlocks;
@@ -367,6 +382,10 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
 // a wrong guess costs one stand-alone mean pass.
 constexpr size_t kSpecSample = size_t(1) << 22;
 constexpr size_t kSpecMinP = size_t(1) << 26;
+// Shorter vectors down to this length guess "the accept set of the previous call" instead
+// (no sample: it would cost too large a share); below it the calls are launch-bound and a
+// writing Gram pass gains nothing.
+constexpr size_t kCarryMinP = size_t(1) << 21;
 
 // Distance in elements between the starts of consecutive runs of the sample for vectors of
 // length P >= kSpecMinP: the runs spread over the whole vector, the last one ends inside it.
@@ -392,17 +411,19 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                int32_t *count, hipStream_t s)
 {
     const double *gram = opt.gram;
-    // Long vectors: guess the accept set from a sample, let the Gram pass
-    // write the mean of that guess while it holds the data on chip, and check the guess afterwards.
-    const bool speculate = !gram && !opt.best_seed && !opt.theta && P >= kSpecMinP &&
-                           ctx->schedule == GAF_SCHEDULE_AUTO;
+    // AUTO: the Gram pass writes the mean of a guessed accept set while it holds the data on chip,
+    // and the guess is checked afterwards. Long vectors: guessed from a sample. Shorter ones:
+    // the previous call's accept set.
+    const bool speculate = !gram && !opt.best_seed && !opt.theta && ctx->schedule == GAF_SCHEDULE_AUTO &&
+                           P >= kCarryMinP;
+    const bool carried = speculate && P < kSpecMinP;
     const bool small = N <= kSmallMaxN;
-    if (speculate) {
-        if (ctx->pred_reset) {
-            prediction_reset_kernel<<<1, 1, 0, s>>>(ctx->pred);
-            if (launched() != GAF_OK) return GAF_EHIP;
-            ctx->pred_reset = false;
-        }
+    if (speculate && ctx->pred_reset) {
+        prediction_reset_kernel<<<1, 1, 0, s>>>(ctx->pred);
+        if (launched() != GAF_OK) return GAF_EHIP;
+        ctx->pred_reset = false;
+    }
+    if (speculate && !carried) {
         const size_t cs = spec_chunk_stride(P);
         gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs)
                               : gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs);
@@ -411,11 +432,14 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
             Timed t(ctx, s, GAF_K_FILTER);
             filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, &ctx->seed_ws->mask[0][0],
                                            &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list,
-                                           kSpecGuess, ctx->pred, fused_min_count<T>(small ? 0 : (N + 15) / 16));
+                                           kSpecGuess, ctx->pred, spec_min_count<T>(N, false));
         }
         if (launched() != GAF_OK) return GAF_EHIP;
-        rc = small ? gram_small<T, true>(ctx, grads, N, P, s, GAF_K_GRAM, out)
-                   : gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out);
+    }
+    if (speculate) {
+        const int carry_n = carried ? N : 0;
+        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s, GAF_K_GRAM, out, 0, carry_n)
+                                    : gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out, 0, carry_n);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     } else if (!gram) {
@@ -438,7 +462,8 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     } else {
         Timed t(ctx, s, GAF_K_FILTER);
         filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted,
-                                       speculate ? kSpecVerify : kSpecNone, ctx->pred);
+                                       !speculate ? kSpecNone : carried ? kSpecVerifyCarried : kSpecVerify,
+                                       ctx->pred, spec_min_count<T>(N, carried));
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     if (opt.dist_matrix) {

@@ -493,6 +493,50 @@ def test_fused_mean_backs_off_after_wrong_guesses(ctx):
             assert torch.equal(x, y), step
 
 
+@pytest.mark.parametrize("N,P,dtype", [(2, (1 << 21) + 7, "f32"), (2, 11_220_132, "bf16"), (5, (1 << 21) + 4097, "f32"),
+                                       (12, (1 << 21) + 3, "f32"), (20, 1 << 21, "bf16"), (40, (1 << 21) + 33, "f32")])
+def test_carried_guess_on_shorter_vectors(ctx, oracle, N, P, dtype):
+    """Below the length where a sample pays, the guess is the previous call's accept set (same N).
+    Three batches: X and a second draw X2 with the same agreement pattern (guess right), Y with
+    another pattern (guess wrong). Every result is checked against the oracle, must equal the
+    two-pass schedule's bit for bit, and the record must follow the hits and misses."""
+    if ctx.schedule_name != "auto":
+        pytest.skip("the fused mean belongs to the AUTO schedule")
+    gen = torch.Generator().manual_seed(1000 + N)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    base = torch.randn(P, generator=gen)
+    def batch(signs):
+        return [(sg * 0.5 * base + 0.8 * torch.randn(P, generator=gen)).to(tdt) for sg in signs]
+    sx = [1 if i % 3 != 2 else -1 for i in range(N)]; sx[0] = 1
+    sy = [1 if i % 2 == 0 else -1 for i in range(N)]
+    batches = {"X": batch(sx), "X2": batch(sx), "Y": batch(sy)}
+    ref, expect, dev = {}, {}, {}
+    for k, g in batches.items():
+        ref[k] = oracle.aggregate(oracle_arrays(g), np.float32(0.9))
+        assert np.all(np.abs(ref[k][2][1:] - np.float32(0.9)) >= MARGIN)
+        dev[k] = [t.cuda() for t in g]
+        gaf.gaf_set_schedule(ctx, "gram")
+        expect[k] = [t.clone() for t in gaf.gaf_aggregate(ctx, dev[k], 0.9)]
+    assert ref["X"][1].tolist() == ref["X2"][1].tolist() != ref["Y"][1].tolist()
+    gaf.gaf_set_schedule(ctx, "auto")
+    # (batch, was a mean written by the Gram pass, was it right, backoff after, penalty after)
+    script = [("X", 0, 0, 0, 1),       # nothing to carry yet
+              ("X2", 1, 1, 0, 1), ("X", 1, 1, 0, 1),
+              ("Y", 1, 0, 1, 2),       # guess X's set, wrong
+              ("Y", 0, 0, 0, 2),       # backing off (the guess itself would have been right)
+              ("Y", 1, 1, 0, 1), ("X", 1, 0, 1, 2), ("X2", 0, 0, 0, 2), ("X", 1, 1, 0, 1)]
+    for step, (k, write, valid, backoff, penalty) in enumerate(script):
+        res = gaf.gaf_aggregate(ctx, dev[k], 0.9)
+        rec = gaf.gaf_fused_mean_record(ctx)
+        assert rec == {"write": write, "valid": valid, "backoff": backoff, "penalty": penalty}, (step, k, rec)
+        check_against_oracle(res, ref[k], dtype)
+        for x, y in zip(res, expect[k]):
+            assert torch.equal(x, y), (step, k)
+    # another batch size does not inherit the guess
+    res = gaf.gaf_aggregate(ctx, dev["X"][: N - 1] if N > 2 else dev["X"] + dev["X"][:1], 0.9)
+    assert gaf.gaf_fused_mean_record(ctx)["write"] == 0
+
+
 @pytest.mark.timeout(600)
 def test_large_full_size(ctx, oracle):
     for seed in range(4):
