@@ -1,6 +1,9 @@
 """Randomised (seeded) sweep over shapes: every batch entry point against the oracle on
 sizes drawn across the kernel variants' boundaries (N around 8/16/32/48/64, P around tile,
-stage and unroll multiples), both dtypes, both schedules."""
+stage and unroll multiples), both dtypes, both schedules. A second sweep uses vectors just long
+enough for the batch call to carry its guess of the accept set from call to call: the contexts
+are shared by all cases, so right guesses (the same batch twice in a row) and wrong ones
+(another case with the same N before it) both occur."""
 import numpy as np
 import pytest
 import torch
@@ -24,6 +27,10 @@ def cases():
         P = max(1, min(P, 600_000))
         dtype = "bf16" if rng.random() < 0.5 else "f32"
         out.append((k, N, P, dtype))
+    for k in range(48, 64):
+        N = int(rng.choice([2, 2, 3, 5, 8, 9, 16, 17, 33, 48]))
+        P = (1 << 21) + int(rng.integers(0, 300_000))
+        out.append((k, N, P, "bf16" if rng.random() < 0.5 else "f32"))
     return out
 
 
