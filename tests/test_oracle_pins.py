@@ -309,3 +309,68 @@ def test_bf16_widening_is_exact(oracle):
     x, y = ref, (t * 3).to(torch.bfloat16).to(torch.float64).numpy()
     d = 1 - (x @ y) / (np.linalg.norm(x) * np.linalg.norm(y))
     assert abs(oracle.cosine_distance(u, v) - d) < 1e-13
+
+
+# ------------------------------ exact rational arithmetic on tiny inputs -----
+# Algorithm 1 decided without any rounding: small integer vectors, every inner
+# product an integer, and "1 - a/sqrt(b) <= tau" settled by comparing squares of
+# rationals (no square root is ever taken). The mean is an exact fraction.
+def _exact_accepts(a, b, tau):
+    """Is 1 - a / sqrt(b) <= tau, for integers a, b >= 0 and a Fraction tau? (b = 0: the
+    zero-norm reading, D = 1.) Returns None when the two sides are exactly equal."""
+    from fractions import Fraction
+    if b == 0:
+        return Fraction(1) <= tau
+    t = 1 - tau                       # accept iff t * sqrt(b) <= a
+    if a == 0 and t == 0:
+        return True                   # D is exactly 1 = tau in any arithmetic: the tie accepts
+    lhs2, rhs2 = t * t * b, Fraction(a * a)
+    if lhs2 == rhs2 and (t >= 0) == (a >= 0):
+        return None
+    if t >= 0:
+        return a >= 0 and lhs2 <= rhs2
+    return a >= 0 or lhs2 >= rhs2
+
+
+def _exact_filter(rows, tau, order):
+    from fractions import Fraction
+    seed = order[0]
+    total = list(rows[seed])
+    accepted = [seed]
+    for i in order[1:]:
+        a = sum(x * y for x, y in zip(total, rows[i]))
+        b = sum(x * x for x in total) * sum(y * y for y in rows[i])
+        ok = _exact_accepts(a, b, tau)
+        if ok is None:
+            return None               # an exact tie: not a case for a floating-point comparison
+        if ok:
+            accepted.append(i)
+            total = [x + y for x, y in zip(total, rows[i])]
+    return accepted, [Fraction(x, len(accepted)) for x in total]
+
+
+def test_exact_rational_brute_force(oracle):
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    checked = rejected_some = accepted_some = 0
+    for trial in range(400):
+        N, P = int(rng.integers(2, 7)), int(rng.integers(1, 7))
+        rows = rng.integers(-4, 5, size=(N, P)).tolist()
+        tau32 = f32(rng.choice([0.5, 0.9, 0.97, 1.0, 1.03, 1.3, 1.9]))
+        tau = Fraction(float(tau32))                      # the binary32 value, exactly
+        exact = _exact_filter(rows, tau, list(range(N)))
+        if exact is None:
+            continue
+        accepted, mean = exact
+        out, mask, dist, c = oracle.aggregate([np.array(r, dtype=f32) for r in rows], tau32)
+        # skip the rare case where a distance is within rounding of tau without being 1 = tau exactly
+        near = np.abs(dist[1:] - float(tau32)) < 1e-12
+        if np.any(near & ~((dist[1:] == 1.0) & (float(tau32) == 1.0))):
+            continue
+        assert [i for i in range(N) if mask[i]] == accepted, (rows, float(tau32))
+        assert c == len(accepted)
+        np.testing.assert_allclose(out, [float(m) for m in mean], rtol=1e-15, atol=1e-300)
+        checked += 1
+        rejected_some += c < N
+        accepted_some += c > 1
+    assert checked > 300 and rejected_some > 50 and accepted_some > 50

@@ -118,3 +118,42 @@ def test_bucketed_reduces_to_plain_and_to_slices(oracle):
         np.testing.assert_allclose(out[offs[b]:offs[b + 1]], o, rtol=1e-13)
         assert mask[b].tolist() == m.tolist() and count[b] == c
         np.testing.assert_allclose(dist[b], d, atol=1e-13)
+
+
+def test_best_seed_and_buckets_against_exact_rational_filter(oracle):
+    """The two variants against the rounding-free filter of test_oracle_pins (integer vectors,
+    comparisons on squares of rationals): every ring rotation, every bucket."""
+    from fractions import Fraction
+    from test_oracle_pins import _exact_filter
+    rng = np.random.default_rng(78)
+    checked = 0
+    for trial in range(200):
+        N, P = int(rng.integers(2, 6)), int(rng.integers(2, 9))
+        rows = rng.integers(-4, 5, size=(N, P)).tolist()
+        tau32 = np.float32(rng.choice([0.9, 0.97, 1.0, 1.03, 1.3]))
+        tau = Fraction(float(tau32))
+        arrs = [np.array(r, dtype=np.float32) for r in rows]
+        # order-indifferent: all N rotations, largest count, lowest seed on ties
+        runs = [_exact_filter(rows, tau, [(s + k) % N for k in range(N)]) for s in range(N)]
+        out, mask, dist, c, seed, counts = oracle.best_seed(arrs, tau32)
+        d_all = np.array([oracle.aggregate([arrs[(s + k) % N] for k in range(N)], tau32)[2][1:] for s in range(N)])
+        near = np.any((np.abs(d_all - float(tau32)) < 1e-12) & ~((d_all == 1.0) & (float(tau32) == 1.0)))
+        if all(r is not None for r in runs) and not near:
+            best = max(range(N), key=lambda s: (len(runs[s][0]), -s))
+            assert counts.tolist() == [len(r[0]) for r in runs]
+            assert seed == best and c == len(runs[best][0])
+            assert sorted(i for i in range(N) if mask[i]) == sorted(runs[best][0])
+            np.testing.assert_allclose(out, [float(m) for m in runs[best][1]], rtol=1e-15, atol=1e-300)
+            checked += 1
+        # buckets: a cut at a random interior point, each side filtered on its own
+        cut = int(rng.integers(1, P))
+        parts = [_exact_filter([r[:cut] for r in rows], tau, list(range(N))),
+                 _exact_filter([r[cut:] for r in rows], tau, list(range(N)))]
+        bout, bmask, bdist, bcount = oracle.bucketed(arrs, tau32, [0, cut, P])
+        bnear = (np.abs(bdist[:, 1:] - float(tau32)) < 1e-12) & ~((bdist[:, 1:] == 1.0) & (float(tau32) == 1.0))
+        if all(p is not None for p in parts) and not np.any(bnear):
+            for b, (acc, mean) in enumerate(parts):
+                assert [i for i in range(N) if bmask[b, i]] == acc and bcount[b] == len(acc)
+            np.testing.assert_allclose(bout, [float(m) for p in parts for m in p[1]], rtol=1e-15, atol=1e-300)
+            checked += 1
+    assert checked > 250
