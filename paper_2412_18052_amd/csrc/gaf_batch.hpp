@@ -111,6 +111,7 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
             pred->penalty = penalty;
             pred->write = wrote ? 1 : 0;
             pred->valid = (wrote && same) ? 1 : 0;
+            pred->next_tile = 0;             // tile counter of the mean launch that follows
             if (carried) {
                 pred->n = N;
                 pred->count = c;
@@ -177,6 +178,9 @@ __global__ __launch_bounds__(64) void seed_select_kernel(const SeedWs *ws, int N
 // registers. Products of widened binary32/bfloat16 values are exact in binary64,
 // every load is a fully coalesced 16-byte (8-byte for bf16) load, and at 8 TB/s
 // the FMAs need under a third of the binary64 issue rate.
+constexpr int kMeanClaim = 4;            // tiles a workgroup of the mean kernel claims per counter access
+constexpr int kMeanQueueBlocks = 2048;   // workgroups of a mean launch that claims its tiles
+constexpr size_t kMeanQueueMinTiles = 32768;   // ... used from this many tiles up (one workgroup per tile below)
 constexpr int kSmallMaxN = 8;
 constexpr int kSmallMaxPairs = kSmallMaxN * (kSmallMaxN + 1) / 2;
 constexpr int kSmallBlocks = 512;       // workgroups of the small-batch Gram kernel (<= kMaxBlocks)
@@ -368,8 +372,9 @@ struct MeanArgs {
     const State *st;                // st->count = c
     float *out;                     // may be NULL in the fused-optimizer form
     size_t P;
-    const Prediction *pred;         // non-NULL: if pred->valid, `out` already holds the result (written by
+    Prediction *pred;               // non-NULL: if pred->valid, `out` already holds the result (written by
                                     // the Gram pass for a guessed accept set that proved right)
+    int claim_tiles;                // workgroups claim their tiles from pred->next_tile (see mean_kernel)
     // fused GAF-SGD step (kSgd): parameters and momentum buffer, in place
     float *theta, *vel;
     float lr, mu, wd;
@@ -396,10 +401,12 @@ __device__ __forceinline__ void sgd_element(float g, float &theta, float &v, flo
 // table/list live in LDS: pointers of all gradients, indices of the accepted ones.
 template <typename T, bool kStream, bool kSgd>
 __device__ __forceinline__ void mean_range(const MeanArgs &a, const void *const *table, const int32_t *list,
-                                           int c, size_t lo, size_t hi, size_t first, size_t stride)
+                                           int c, size_t lo, size_t hi, size_t first, size_t stride,
+                                           size_t tile_end = ~size_t(0))
 {
     const float inv_c = 1.0f / (float)c;
-    const size_t ntiles = (hi - lo + kTile - 1) / kTile;
+    const size_t all_tiles = (hi - lo + kTile - 1) / kTile;
+    const size_t ntiles = all_tiles < tile_end ? all_tiles : tile_end;
     float *out = a.out;
     const bool step = kSgd && c > 1;
     if (kSgd && !step && !out) return;      // skipped step, nothing else asked for
@@ -490,7 +497,26 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
         list[threadIdx.x] = int(threadIdx.x) < c ? a.accepted_list[threadIdx.x] : 0;
     }
     __syncthreads();
-    mean_range<T, kStream, kSgd>(a, table, list, c, 0, a.P, blockIdx.x, gridDim.x);
+    if (!a.claim_tiles) {
+        mean_range<T, kStream, kSgd>(a, table, list, c, 0, a.P, blockIdx.x, gridDim.x);
+        return;
+    }
+    // Long vectors after a guess: a bounded grid (a launch that finds the result in place must
+    // stay cheap, and a workgroup per tile would cost 50 us just to dispatch at 1e9 elements)
+    // whose workgroups claim kMeanClaim tiles at a time from a counter -- no sums cross tiles,
+    // so which workgroup takes which tile does not change a bit of the result, and the
+    // dispatcher-like balance is worth 10-15 % over a fixed split. The counter was cleared by
+    // the filter launch that verified the guess.
+    __shared__ unsigned claimed;
+    const size_t ntiles = (a.P + kTile - 1) / kTile;
+    for (;;) {
+        if (threadIdx.x == 0) claimed = atomicAdd(&a.pred->next_tile, (unsigned)kMeanClaim);
+        __syncthreads();
+        const size_t t0 = claimed;
+        __syncthreads();
+        if (t0 >= ntiles) return;       // every workgroup gets here once the tiles run out
+        mean_range<T, kStream, kSgd>(a, table, list, c, 0, a.P, t0, 1, t0 + kMeanClaim);
+    }
 }
 
 // ---- bucketed filtering in three launches (small batches) -------------------

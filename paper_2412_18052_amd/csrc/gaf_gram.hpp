@@ -88,6 +88,7 @@ struct Prediction {
     int32_t backoff;   // calls left during which no guess is written, after a wrong one
     int32_t penalty;   // backoff imposed by the next wrong guess: doubles per miss up to kSpecMaxPenalty,
                        // halves per hit; 0 = never used, treated as 1
+    uint32_t next_tile;  // work counter of the mean launch after a guess (cleared by the verifying filter)
 };
 
 // Guess carried over from the previous call (carry_n = this call's N): is it usable, and does

@@ -48,6 +48,18 @@ inline int pass_blocks(size_t P, int cap = kMaxBlocks)
     return static_cast<int>((ntiles + iters - 1) / iters);
 }
 
+// Workgroups for a pass that writes and has no sums to combine afterwards (masked mean,
+// update, copy): one per tile. Measured on 1 and 4 GiB copies and 2..9-stream sums, workgroups
+// that take one tile and end run 7-19 % faster than 2048 workgroups looping over the tiles
+// (6.0-6.5 against 5.0-5.9 TB/s; the longer the vectors the larger the gap): the dispatcher
+// evens out what a fixed split cannot. Passes that leave partial sums keep the bounded grid
+// above (their summation order is tied to it).
+inline int tile_blocks(size_t P)
+{
+    const size_t ntiles = (P + kTile - 1) / kTile;
+    return static_cast<int>(ntiles < (size_t(1) << 22) ? ntiles : (size_t(1) << 22));
+}
+
 gaf_status check_ctx(const gaf_ctx *ctx)
 {
     if (!ctx) return GAF_EINVAL;
@@ -119,7 +131,7 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
         a.count_out = count;
         {
             Timed t(ctx, s, GAF_K_UPDATE);
-            update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+            update_kernel<T, kStream><<<tile_blocks(P), block, 0, s>>>(a);
         }
         return launched();
     }
@@ -171,7 +183,7 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
     a.count_out = nullptr;
     {
         Timed t(ctx, s, GAF_K_UPDATE);
-        update_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+        update_kernel<T, kStream><<<tile_blocks(P), block, 0, s>>>(a);
     }
     return launched();
 }
@@ -211,13 +223,14 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
 // Smallest predicted accept count for which the Gram pass writes the mean itself. Mixing the
 // 4 P written bytes into the reading pass added 0.6 to 2.5 ms to the measured calls (batches of
 // 32 GB), nearly independent of the count c, while the stand-alone mean costs (c s + 4) P bytes
-// at about 5.2 TB/s; below these measured break-even counts the stand-alone mean is the cheaper
-// one (by up to 15% of the call at c = 1). groups = 0 means the small-batch (N <= 8) kernel.
+// at about 5.85 TB/s; below these break-even counts (from the measured pass times) the
+// stand-alone mean is the cheaper one (by up to 15% of the call at c = 1).
+// groups = 0 means the small-batch (N <= 8) kernel.
 template <typename T>
 constexpr int fused_min_count(int groups)
 {
-    constexpr int bf16_min[5] = {2, 4, 6, 8, 10};
-    constexpr int f32_min[5] = {2, 4, 7, 7, 7};
+    constexpr int bf16_min[5] = {3, 6, 9, 12, 16};
+    constexpr int f32_min[5] = {2, 4, 8, 7, 8};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
 // The same for a batch of N gradients. A guess carried over from the previous call is used on
@@ -486,11 +499,15 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     m.mu = opt.mu;
     m.wd = opt.wd;
     {
+        // long vectors after a guess: the launch may have nothing to do, so a bounded grid that
+        // claims its tiles from a counter
+        m.claim_tiles = speculate && size_t(tile_blocks(P)) >= kMeanQueueMinTiles;
+        const int nb = m.claim_tiles ? kMeanQueueBlocks : tile_blocks(P);
         Timed t(ctx, s, GAF_K_MEAN);
         if (opt.theta)
-            mean_kernel<T, kStream, true><<<pass_blocks(P), kBlock, 0, s>>>(m);
+            mean_kernel<T, kStream, true><<<nb, kBlock, 0, s>>>(m);
         else
-            mean_kernel<T, kStream, false><<<pass_blocks(P), kBlock, 0, s>>>(m);
+            mean_kernel<T, kStream, false><<<nb, kBlock, 0, s>>>(m);
     }
     return launched();
 }
