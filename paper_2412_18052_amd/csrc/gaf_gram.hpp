@@ -36,7 +36,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 constexpr int kGramGroups = 4;          // row groups per launch
 constexpr int kGramRows = 16 * kGramGroups;
 constexpr int kGramFlush = 8;           // stages between binary32 -> binary64 flushes
-constexpr int kGramBlocks = 512;        // workgroups per launch (fixed: the summation order depends on it)
+constexpr int kGramBlocks = 512;        // (virtual) workgroups per launch (fixed: the summation order depends on it)
 constexpr int kGramTile = 16 * 16;      // entries per tile
 constexpr int kGramMaxTiles = 10;       // 4 groups: 4 diagonal + 6 off-diagonal tiles
 constexpr int kGramPad = 4;             // LDS row padding, 32-bit words
@@ -186,9 +186,24 @@ __device__ __forceinline__ void mma_bf16(const bf16x8_t &x, const bf16x8_t &y, f
 // instead of binary32 MFMAs. Used where the binary32 matrix rate would bind
 // (three or four row groups); with one or two groups the kernel is memory bound
 // either way and the split would only add vector-ALU work.
-template <typename T, int NG, int kMode, bool kMean = false, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
+//
+// kHalves = 2: a workgroup is two halves of 256 threads; each half is one "virtual workgroup"
+// with its own stage buffers, stages and partial tiles (the decomposition of the work, and so
+// every bit of the result, is the same as with kHalves = 1 and twice the grid) and the halves
+// share nothing but the barriers. That is the point: two independent 256-thread workgroups on
+// one compute unit do not progress evenly -- measured with the writing bf16 kernel, the one
+// dispatched first ends 15 % before the other, which then runs alone at half the unit's
+// capacity; halves of one workgroup are held together by the barrier of every stage (-4.5 % on
+// that kernel; the read-only and the binary32 kernels lose 3-6 % to the lockstep and keep
+// kHalves = 1).
+template <typename T, int NG, int kMode, bool kMean = false, int kHalves = 1,
+          bool kSplit = (sizeof(T) == 4 && NG >= 3)>
+__global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
 {
+    static_assert(kHalves == 1 || kHalves == 2, "one or two virtual workgroups per workgroup");
+    const int half = kHalves == 1 ? 0 : int(threadIdx.x) / kBlock;
+    const int tid = kHalves == 1 ? int(threadIdx.x) : int(threadIdx.x) % kBlock;
+    const size_t vblock = size_t(blockIdx.x) * kHalves + half;       // virtual workgroup
     typedef TileList<NG, kMode> Tiles;
     constexpr int NT = Tiles::count;
     constexpr int M = gram_stage_m(NG);
@@ -200,11 +215,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     constexpr int kInner = sizeof(T) == 4 ? 4 : 1;          // MFMAs per 16-byte register
     static_assert(2 * kStageWords * 4 >= NT * kGramTile * 8, "stage buffers are reused for the final combine");
 
-    __shared__ __attribute__((aligned(16))) uint32_t stage[2 * kStageWords];
+    __shared__ __attribute__((aligned(16))) uint32_t stage_all[kHalves][2 * kStageWords];
     __shared__ const void *row_table[kGramRows];
     __shared__ int32_t pred_rows[kGramRows];
+    uint32_t *const stage = stage_all[half];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, sub = lane >> 4;
 
     // pointer table into LDS, read with compile-time indices so that it stays in
@@ -241,7 +257,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
 
     const size_t P = a.P;
     const size_t nfull = P / kStageElems;
-    const size_t G = gridDim.x;
+    const size_t G = size_t(gridDim.x) * kHalves;               // virtual workgroups
 
     floatx4 acc[NT];
     double tot[NT][4];
@@ -327,7 +343,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         constexpr int kQuads = int(kStageElems / 4);
         const float inv_c = 1.0f / (float)c_pred;
         const size_t e_base = s * kStageElems;
-        for (int q = threadIdx.x; q < kQuads; q += kBlock) {
+        for (int q = tid; q < kQuads; q += kBlock) {
             f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
             for (int k = 0; k < c_pred; ++k) {
                 const uint32_t *src = &stage[buf * kStageWords + pred_rows[k] * kRowWords];
@@ -366,36 +382,81 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
             }
     };
 
-    size_t s = blockIdx.x;
     int buf = 0, since_flush = 0;
-    if (s < nfull) {
-        gload(s);
-        lstore(0);
-        __syncthreads();
-        while (s + G < nfull) {
-            gload(s + G);              // in flight during the MFMAs below
+    if constexpr (kHalves == 1) {
+        // stages blockIdx.x, blockIdx.x + G, ...
+        size_t s = blockIdx.x;
+        if (s < nfull) {
+            gload(s);
+            lstore(0);
+            __syncthreads();
+            while (s + G < nfull) {
+                gload(s + G);              // in flight during the MFMAs below
+                compute(buf);
+                if (kMean && write_mean) mean_stage(buf, s);
+                if (++since_flush == kGramFlush) {
+                    since_flush = 0;
+                    flush();
+                }
+                lstore(buf ^ 1);           // the other buffer was last read before the previous barrier
+                __syncthreads();
+                buf ^= 1;
+                s += G;
+            }
             compute(buf);
             if (kMean && write_mean) mean_stage(buf, s);
-            if (++since_flush == kGramFlush) {
-                since_flush = 0;
-                flush();
+        }
+        // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
+        if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
+            __syncthreads();
+            gload_guarded(nfull);
+            lstore(0);
+            __syncthreads();
+            compute(0);
+            if (kMean && write_mean) mean_stage(0, nfull);
+        }
+    } else {
+        // Virtual workgroup v takes stages v, v + G, ... (the same stages, in the same order and
+        // with the same flush points as a workgroup of the branch above). The halves of a workgroup
+        // may differ by one stage while the barriers are common: both run the trip count of the
+        // first half, and a half without a stage left idles through the barriers.
+        const size_t first = size_t(blockIdx.x) * kHalves;
+        const size_t n_mine = nfull > vblock ? (nfull - vblock + G - 1) / G : 0;
+        const size_t n_trip = nfull > first ? (nfull - first + G - 1) / G : 0;
+        if (n_mine > 0) {
+            gload(vblock);
+            lstore(0);
+        }
+        __syncthreads();
+        for (size_t k = 0; k < n_trip; ++k) {
+            const size_t s = vblock + k * G;
+            const bool has = k < n_mine, has_next = k + 1 < n_mine;
+            if (has_next) gload(s + G);
+            if (has) {
+                compute(buf);
+                if (kMean && write_mean) mean_stage(buf, s);
+                if (has_next && ++since_flush == kGramFlush) {
+                    since_flush = 0;
+                    flush();
+                }
             }
-            lstore(buf ^ 1);           // the other buffer was last read before the previous barrier
+            if (has_next) lstore(buf ^ 1);
             __syncthreads();
             buf ^= 1;
-            s += G;
         }
-        compute(buf);
-        if (kMean && write_mean) mean_stage(buf, s);
-    }
-    // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
-    if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
-        __syncthreads();
-        gload_guarded(nfull);
-        lstore(0);
-        __syncthreads();
-        compute(0);
-        if (kMean && write_mean) mean_stage(0, nfull);
+        // ragged tail: one virtual workgroup (the condition of the barrier is uniform over the workgroup)
+        if (nfull * kStageElems < P && blockIdx.x == (nfull % G) / kHalves) {
+            const bool tail_mine = vblock == nfull % G;
+            if (tail_mine) {
+                gload_guarded(nfull);
+                lstore(0);
+            }
+            __syncthreads();
+            if (tail_mine) {
+                compute(0);
+                if (kMean && write_mean) mean_stage(0, nfull);
+            }
+        }
     }
     flush();
 
@@ -416,8 +477,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         }
     }
     __syncthreads();
-    double *out = a.ws + size_t(blockIdx.x) * kGramMaxTiles * kGramTile;
-    for (int e = threadIdx.x; e < NT * kGramTile; e += kBlock) out[e] = comb[e];
+    double *out = a.ws + vblock * kGramMaxTiles * kGramTile;
+    for (int e = tid; e < NT * kGramTile; e += kBlock) out[e] = comb[e];
 }
 
 // Adds the per-workgroup tiles in workgroup order and scatters them into the

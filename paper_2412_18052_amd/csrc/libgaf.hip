@@ -233,6 +233,15 @@ constexpr int fused_min_count(int groups)
     constexpr int f32_min[5] = {2, 4, 8, 7, 8};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
+// Halves per workgroup of the Gram kernel when it also writes the mean (see gram_kernel):
+// two where it was measured faster (bf16 rows in one or two groups: -7 % and -8 %), one where
+// it made no difference (binary32, one group) or cost 3-12 % (everything wider).
+template <typename T>
+constexpr int fused_gram_halves(int groups)
+{
+    return sizeof(T) == 2 && groups <= 2 ? 2 : 1;
+}
+
 // The same for a batch of N gradients. A guess carried over from the previous call is used on
 // shorter vectors, where the small-batch kernel gains from writing even a one-gradient "mean"
 // (the stand-alone pass would cost a launch and a second read of that gradient).
@@ -279,8 +288,9 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     g.chunk_stride = chunk_stride;
     {
         Timed t(ctx, s, id);
+        constexpr int kHalves = fused_gram_halves<T>(NG);
         if (mean_out && kMode == kFull)
-            gram_kernel<T, NG, kFull, true><<<kGramBlocks, kBlock, 0, s>>>(g);
+            gram_kernel<T, NG, kFull, true, kHalves><<<kGramBlocks / kHalves, kBlock * kHalves, 0, s>>>(g);
         else
             gram_kernel<T, NG, kMode><<<kGramBlocks, kBlock, 0, s>>>(g);
     }
