@@ -207,7 +207,10 @@ __host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlo
 // matrix-core Gram kernel for the idea); the plain filter visits in index order,
 // so adding the predicted rows in index order reproduces the stand-alone mean
 // kernel bit for bit.
-template <typename T, int N, bool kStream, bool kMean = false>
+// kHalves = 2 (see the matrix-core Gram kernel): the workgroup is two halves of kBlock threads,
+// each a virtual workgroup of its own (`first`, `out` and the tiles belong to the calling half)
+// that share only a barrier per tile, which keeps the two from drifting apart.
+template <typename T, int N, bool kStream, bool kMean = false, int kHalves = 1>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
                                                  size_t first, size_t stride, double *out, size_t out_stride,
                                                  const Prediction *pred = nullptr, float *mean_out = nullptr,
@@ -218,7 +221,11 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     constexpr size_t tile = small_gram_tile(N);
     constexpr size_t kTilesPerChunk = kSampleChunk / tile;
     static_assert(kSampleChunk % tile == 0, "a sample run is a whole number of tiles");
-    __shared__ double lds[NP][kWaves];
+    static_assert(kHalves == 1 || kHalves == 2, "one or two virtual workgroups per workgroup");
+    __shared__ double lds_all[kHalves][NP][kWaves];
+    const int half = kHalves == 1 ? 0 : int(threadIdx.x) / kBlock;
+    const int tid = kHalves == 1 ? int(threadIdx.x) : int(threadIdx.x) % kBlock;
+    double(*const lds)[kWaves] = lds_all[half];
 
     const T *row[N];
 #pragma unroll
@@ -255,12 +262,21 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
     };
 
     const size_t ntiles = (hi - lo + tile - 1) / tile;
-    for (size_t t = first; t < ntiles; t += stride) {
+    // tiles first, first + stride, ...; with two halves both run the trip count of the first half
+    // (it has the lower `first`), and a half without a tile left only joins the barrier
+    const size_t first0 = first - size_t(half);
+    const size_t n_trip = ntiles > first0 ? (ntiles - first0 + stride - 1) / stride : 0;
+    for (size_t trip = 0; trip < n_trip; ++trip) {
+        const size_t t = first + trip * stride;
+        if (kHalves > 1) {
+            __syncthreads();
+            if (t >= ntiles) continue;
+        }
         // sampling launch (chunk_stride != 0): [lo, hi) indexes the sample, whose run r of
         // kSampleChunk elements starts at element r * chunk_stride of the vectors
         const size_t tile_at = chunk_stride ? (t / kTilesPerChunk) * chunk_stride + (t % kTilesPerChunk) * tile
                                             : t * tile;
-        const size_t base = lo + tile_at + size_t(threadIdx.x) * 4;
+        const size_t base = lo + tile_at + size_t(tid) * 4;
         if (lo + (t + 1) * tile <= hi) {
             float4 v[U][N];
 #pragma unroll
@@ -318,27 +334,29 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
         }
     }
     // workgroup sums: DPP tree per wavefront, wavefronts added in order
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
         const double v = wave_sum(acc[k]);
         if (lane == 0) lds[k][wave] = v;
     }
     __syncthreads();
-    if (threadIdx.x < NP) {
-        double v = lds[threadIdx.x][0];
+    if (tid < NP) {
+        double v = lds[tid][0];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) v += lds[threadIdx.x][w];
-        out[size_t(threadIdx.x) * out_stride] = v;
+        for (int w = 1; w < kWaves; ++w) v += lds[tid][w];
+        out[size_t(tid) * out_stride] = v;
     }
 }
 
-template <typename T, int N, bool kStream, bool kMean = false>
-__global__ __launch_bounds__(kBlock) void gram_small_kernel(SmallGramArgs a)
+template <typename T, int N, bool kStream, bool kMean = false, int kHalves = 1>
+__global__ __launch_bounds__(kBlock *kHalves) void gram_small_kernel(SmallGramArgs a)
 {
-    // partials laid out [pair][kMaxBlocks]
-    gram_small_range<T, N, kStream, kMean>(a.rows, 0, a.P, blockIdx.x, gridDim.x, a.partials + blockIdx.x,
-                                           kMaxBlocks, a.pred, a.mean_out, a.chunk_stride, a.carry_n, a.min_count);
+    // partials laid out [pair][kMaxBlocks], one column per virtual workgroup
+    const size_t vblock = size_t(blockIdx.x) * kHalves + (kHalves == 1 ? 0 : threadIdx.x / kBlock);
+    gram_small_range<T, N, kStream, kMean, kHalves>(a.rows, 0, a.P, vblock, size_t(gridDim.x) * kHalves,
+                                                    a.partials + vblock, kMaxBlocks, a.pred, a.mean_out,
+                                                    a.chunk_stride, a.carry_n, a.min_count);
 }
 
 // One workgroup per pair (i <= j): adds that pair's per-workgroup partial inner
