@@ -188,11 +188,18 @@ gaf_status aggregate_impl(gaf_ctx *ctx, const void *const *grads, int N, size_t 
     return launched();
 }
 
+// Streaming visits of vectors from this length on take three launches (reduce, decide, update)
+// instead of two (reduce, decide+update).
+constexpr size_t kStepSplitMinP = size_t(1) << 26;
+
 template <typename T, bool kStream>
 gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                      float tau, float *cos_out, uint8_t *acc_out, hipStream_t s)
 {
-    const dim3 grid(pass_blocks(P, kStepBlocks)), block(kBlock);
+    // Long vectors: the update runs one workgroup per tile (see tile_blocks), which is worth more
+    // than the decision launch it would otherwise absorb; the reducing pass then uses the full grid.
+    const bool long_vector = P >= kStepSplitMinP;
+    const dim3 grid(pass_blocks(P, long_vector ? kMaxBlocks : kStepBlocks)), block(kBlock);
     PassArgs a{};
     a.P = P;
     a.st = ctx->st;
@@ -207,15 +214,28 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
         reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
     }
     if (launched() != GAF_OK) return GAF_EHIP;
+    a.cos_out = cos_out;
+    a.mask_out = acc_out;
+    if (long_vector) {
+        {
+            Timed t(ctx, s, GAF_K_DECIDE);
+            decide_kernel<<<1, block, 0, s>>>(a, grid.x);     // reads *count: 0 means g_i seeds
+        }
+        if (launched() != GAF_OK) return GAF_EHIP;
+    }
     a.pend = g_i;
     a.next = nullptr;
     a.count_in = nullptr;
-    a.cos_out = cos_out;
-    a.mask_out = acc_out;
     a.count_out = count;
     {
         Timed t(ctx, s, GAF_K_UPDATE);
-        decide_update_kernel<T, kStream><<<grid, block, 0, s>>>(a, grid.x);
+        if (long_vector) {
+            a.cos_out = nullptr;
+            a.mask_out = nullptr;
+            update_kernel<T, kStream><<<tile_blocks(P), block, 0, s>>>(a);
+        } else {
+            decide_update_kernel<T, kStream><<<grid, block, 0, s>>>(a, grid.x);
+        }
     }
     return launched();
 }

@@ -309,6 +309,27 @@ def test_streaming_state_is_resumable(ctx, oracle):
     assert int(count2.item()) == ref[3] and rel_l2(accum2.cpu().numpy(), ref[0]) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_streaming_long_vectors(ctx, oracle, dtype):
+    """From 2^26 elements on a streaming visit is three launches (reduce, decide, update with one
+    workgroup per tile) instead of two; same results, including the seeding first visit."""
+    P, N = (1 << 26) + 4099, 6
+    gen = torch.Generator(device="cuda").manual_seed(26)
+    base = torch.randn(P, generator=gen, device="cuda")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    grads = [(sg * 0.4 * base + 0.9 * torch.randn(P, generator=gen, device="cuda")).to(tdt)
+             for sg in (1, 1, -1, 1, -1, 1)]
+    del base
+    ref = _oracle_sequential_from_device(oracle, grads, 0.95)
+    assert np.all(np.abs(ref[2][1:] - np.float32(0.95)) >= MARGIN)
+    assert ref[1].tolist() == [1, 1, 0, 1, 0, 1]
+    accum = torch.empty(P, device="cuda"); count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dist = torch.empty(N, device="cuda"); mask = torch.empty(N, dtype=torch.uint8, device="cuda")
+    for i, g in enumerate(grads):
+        gaf.gaf_step(ctx, accum, count, g, 0.95, dist[i:i + 1], mask[i:i + 1])
+    check_against_oracle((accum, mask, dist, count), ref, dtype)
+
+
 # ------------------------------------------------------------- pairwise -------
 @pytest.mark.parametrize("N,P,dtype", [(1, 1000, "f32"), (2, 31, "f32"), (5, 33, "f32"), (32, 4097, "f32"),
                                        (33, 70_001, "f32"), (64, 100_003, "bf16"), (70, 50_021, "f32"),
