@@ -11,6 +11,15 @@
 // instead of one read of the aggregate per visit and a rewrite per acceptance.
 // Same mask, distances and macro-gradient as the sequential schedule up to
 // rounding; the distances here come from exact-product binary64 sums.
+//
+// The second read of the accepted gradients is only needed because the accept
+// set is unknown while the Gram pass has the data on chip. Where it pays, the
+// set is therefore guessed beforehand (from a sample of the vectors, or from
+// the previous call), the Gram pass writes the mean of the guess as it goes
+// (kMean variants), the filter launch on the full matrix verifies the guess
+// and keeps a record of hits and misses, and the mean kernel only runs when
+// the guess was wrong or not used: see Prediction, filter_kernel, mean_kernel.
+// Whatever is guessed, the results are those of the two-pass form bit for bit.
 #pragma once
 #include "gaf_device.hpp"
 #include "gaf_gram.hpp"
