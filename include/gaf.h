@@ -65,7 +65,7 @@ typedef enum {
     GAF_EALIGN = 2,       /* a DEVICE vector pointer is not 16-byte aligned */
     GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace */
     GAF_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
-    GAF_EUNSUPPORTED = 5, /* unknown dtype */
+    GAF_EUNSUPPORTED = 5, /* unknown dtype, or N outside the range of the requested form */
     GAF_EDEVICE = 6       /* the context's device is not the calling thread's current device */
 } gaf_status;
 

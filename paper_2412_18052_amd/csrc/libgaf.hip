@@ -698,7 +698,7 @@ const char *gaf_strerror(gaf_status status)
     case GAF_EALIGN: return "device vector pointer is not 16-byte aligned";
     case GAF_ENOMEM: return "out of device memory";
     case GAF_EHIP: return "HIP runtime call or kernel launch failed";
-    case GAF_EUNSUPPORTED: return "unsupported element type";
+    case GAF_EUNSUPPORTED: return "unsupported element type, or batch size outside the range of the requested form";
     case GAF_EDEVICE: return "context's device is not the current device";
     }
     return "unknown status";
