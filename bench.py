@@ -437,6 +437,8 @@ def main():
                                 "mean_written_by_gram_pass": sum(r["write"] for r in records),
                                 "right": sum(r["valid"] for r in records), "steps": len(records)}
                                if records else None),
+                   "generator": "g_i = a_i (s_i sqrt(rho_i) c + sqrt(1 - rho_i) z_i); rho, s, a from numpy Philox keyed by "
+                                "the seed, c and z_i from a torch.Generator on the device (" + w.noise + "); see workloads.py",
                    "algorithmic_bytes_per_step": step_bytes,
                    "launches_per_step": launches_per_step, "generate_seconds": gen_s},
         "roofline": roof,
