@@ -162,7 +162,12 @@ typedef enum {
     GAF_SCHEDULE_GRAM = 2
 } gaf_schedule;
 
-/* Also clears the context's record of guesses (the next batch call enqueues the clearing). */
+/*
+ * Also clears the context's record of guesses: the next batch call that guesses
+ * enqueues the clearing ahead of its own kernels (so a call captured into a
+ * graph right after this one carries the clearing with it and forgets the
+ * record at every replay; run one batch call eagerly first to avoid that).
+ */
 gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule);
 
 /*
