@@ -385,6 +385,8 @@ def test_argument_errors(ctx):
     assert lib.gaf_step(ctx.handle, op, count.data_ptr(), xp + 2, P, 1, 1.0, None, None, None) == gaf.GAF_EALIGN
     assert lib.gaf_step(ctx.handle, op, None, xp, P, 0, 1.0, None, None, None) == gaf.GAF_EINVAL
     assert lib.gaf_pairwise(ctx.handle, (ctypes.c_void_p * 1)(xp), 1, P, 0, None, None, None) == gaf.GAF_EINVAL
+    assert lib.gaf_fused_mean_record(ctx.handle, None) == gaf.GAF_EINVAL
+    assert lib.gaf_fused_mean_record(None, (ctypes.c_int32 * 4)()) == gaf.GAF_EINVAL
     torch.cuda.synchronize()
     with pytest.raises(gaf.GafError):
         gaf.gaf_aggregate(ctx, [x[1:P + 1], x[1:P + 1]], 1.0)
