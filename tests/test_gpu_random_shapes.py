@@ -75,3 +75,70 @@ def test_random_shape(ctxs, oracle, k, N, P, dtype):
         for i, g in enumerate(dev):
             gaf.gaf_step(ctx, accum, cnt, g, float(tau), sd[i:i + 1], sm[i:i + 1])
         check_against_oracle((accum, sm, sd, cnt), ref, dtype)
+
+
+
+def long_cases():
+    rng = np.random.default_rng(20250101)
+    out = []
+    for k, N in enumerate([2, 3, 5, 8, 9, 16, 17, 33, 48, 64, 2, 16]):
+        P = (1 << 26) + int(rng.integers(0, 100_000))
+        out.append((k, N, P, "bf16" if rng.random() < 0.5 else "f32"))
+    return out
+
+
+@pytest.fixture(scope="module")
+def long_ctxs():
+    c = {"auto": gaf.gaf_create(max_P=(1 << 26) + 100_000, max_N=64),     # never touched: keeps its record
+         "other": gaf.gaf_create(max_P=(1 << 26) + 100_000, max_N=64)}
+    yield c
+    torch.cuda.synchronize()
+    for v in c.values():
+        gaf.gaf_destroy(v)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("k,N,P,dtype", long_cases())
+def test_random_long_vectors_guessing_changes_nothing(long_ctxs, k, N, P, dtype):
+    """Vectors long enough for the accept set to be guessed from a sample (too long for the oracle
+    at these batch sizes). One AUTO context lives through all cases, so its record of guesses,
+    backoff included, is in whatever state the earlier cases left. The first gradients behind the
+    seed are built to sit within the sample's error of tau, so that guesses do go wrong. Whatever
+    was guessed, the AUTO result must equal the two-pass schedule's bit for bit, and the
+    sequential schedule must agree where its distances keep a margin from tau."""
+    gen = torch.Generator(device="cuda").manual_seed(5000 + k)
+    hrng = np.random.default_rng(9000 + k)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    tau = 0.95
+    base = torch.randn(P, generator=gen, device="cuda")
+    grads = []
+    for i in range(N):
+        if i == 0:
+            a = 0.4
+        elif i <= 2:
+            a = 0.111 * (1.0 + hrng.normal() * 2e-3)      # cosine to the seed close to 1 - tau
+        else:
+            a = 0.4 if hrng.random() < 0.6 else -0.4
+        grads.append((a * base + 0.9 * torch.randn(P, generator=gen, device="cuda")).to(tdt))
+    del base
+    auto, other = long_ctxs["auto"], long_ctxs["other"]
+    gaf.gaf_set_schedule(other, "gram")
+    ref = [t.clone() for t in gaf.gaf_aggregate(other, grads, tau)]
+    gaf.gaf_set_schedule(other, "sequential")
+    seq = [t.clone() for t in gaf.gaf_aggregate(other, grads, tau)]
+    records = []
+    for rep in range(3):
+        res = gaf.gaf_aggregate(auto, grads, tau)
+        records.append(gaf.gaf_fused_mean_record(auto))
+        for x, y in zip(res, ref):
+            assert torch.equal(x, y), (k, rep, records)
+    d = ref[2].cpu().numpy().astype(np.float64)
+    clear = np.abs(d - np.float32(tau)) >= 5e-4
+    m_ref, m_seq = ref[1].cpu().numpy(), seq[1].cpu().numpy()
+    first_unclear = int(np.argmin(clear)) if not clear.all() else N
+    # up to the first borderline gradient both schedules have seen the same history
+    assert np.array_equal(m_ref[:first_unclear], m_seq[:first_unclear]), (d, m_ref, m_seq)
+    if clear.all():
+        assert int(ref[3].item()) == int(seq[3].item())
+        assert np.max(np.abs(d - seq[2].cpu().numpy())) <= 1e-5
+        assert rel_l2(seq[0].cpu().numpy(), ref[0].cpu().numpy()) <= OUT_RTOL[dtype]
