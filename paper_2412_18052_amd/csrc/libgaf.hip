@@ -243,14 +243,15 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
 // Smallest predicted accept count for which the Gram pass writes the mean itself. Mixing the
 // 4 P written bytes into the reading pass added 0.6 to 2.5 ms to the measured calls (batches of
 // 32 GB), nearly independent of the count c, while the stand-alone mean costs (c s + 4) P bytes
-// at about 5.85 TB/s; below these break-even counts (from the measured pass times) the
-// stand-alone mean is the cheaper one (by up to 15% of the call at c = 1).
+// at about 5.85 TB/s; below these break-even counts (smallest c at which the whole call was
+// measured faster with the fused write, 32 GB batches) the stand-alone mean is the cheaper one
+// (by up to 15% of the call at c = 1).
 // groups = 0 means the small-batch (N <= 8) kernel.
 template <typename T>
 constexpr int fused_min_count(int groups)
 {
-    constexpr int bf16_min[5] = {3, 6, 9, 12, 16};
-    constexpr int f32_min[5] = {2, 4, 8, 7, 8};
+    constexpr int bf16_min[5] = {2, 5, 9, 8, 12};
+    constexpr int f32_min[5] = {1, 4, 8, 8, 7};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
 // Halves per workgroup of the Gram kernel when it also writes the mean (see gram_kernel):

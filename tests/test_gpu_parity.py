@@ -409,7 +409,7 @@ def _oracle_sequential_from_device(oracle, grads, tau):
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("N,dtype,pattern", [(10, "bf16", "mixed"), (10, "f32", "mixed"), (40, "bf16", "mixed"),
                                              (5, "f32", "mixed"), (5, "bf16", "mixed"),
-                                             (10, "bf16", "few"), (10, "f32", "few"), (5, "f32", "few")])
+                                             (10, "bf16", "few"), (10, "f32", "few"), (5, "bf16", "few")])
 def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
     """Long vectors on the matrix-core path: the accept set is guessed from a sample of 2^22
     elements (256 evenly spaced runs of 2^14, as the header documents) and the Gram pass writes
