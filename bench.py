@@ -90,7 +90,7 @@ def main():
                     help="target CPU time of the oracle baseline sample (0 disables it)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+        sys.exit("bench.py: the library runs on one GPU only (no collectives, no sharding); "
                  "use --gpus 1")
 
     import numpy as np
