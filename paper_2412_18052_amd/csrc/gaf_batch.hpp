@@ -87,6 +87,16 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
                                                     int32_t *accepted_list, int spec = kSpecNone,
                                                     Prediction *pred = nullptr, int min_count = 0)
 {
+    if (spec == kSpecGuess && pred->backoff > 0) {
+        // backing off: the sampling launch did not run either, there is no guess
+        if (threadIdx.x == 0) {
+            pred->count = 0;
+            pred->write = 0;
+            pred->valid = 0;
+            pred->n = N;
+        }
+        return;
+    }
     const int c = run_filter(gram, N, 0, tau, mask, cos_dist, accepted_list);
     if (threadIdx.x == 0) {
         count[0] = c;
@@ -361,6 +371,8 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
 template <typename T, int N, bool kStream, bool kMean = false, int kHalves = 1>
 __global__ __launch_bounds__(kBlock *kHalves) void gram_small_kernel(SmallGramArgs a)
 {
+    // a sampling launch has nothing to do while a backoff runs: no guess will be written
+    if (a.chunk_stride != 0 && a.pred->backoff > 0) return;
     // partials laid out [pair][kMaxBlocks], one column per virtual workgroup
     const size_t vblock = size_t(blockIdx.x) * kHalves + (kHalves == 1 ? 0 : threadIdx.x / kBlock);
     gram_small_range<T, N, kStream, kMean, kHalves>(a.rows, 0, a.P, vblock, size_t(gridDim.x) * kHalves,

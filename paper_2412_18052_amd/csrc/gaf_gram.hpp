@@ -204,6 +204,8 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
     const int half = kHalves == 1 ? 0 : int(threadIdx.x) / kBlock;
     const int tid = kHalves == 1 ? int(threadIdx.x) : int(threadIdx.x) % kBlock;
     const size_t vblock = size_t(blockIdx.x) * kHalves + half;       // virtual workgroup
+    // a sampling launch has nothing to do while a backoff runs: no guess will be written
+    if (a.chunk_stride != 0 && a.pred->backoff > 0) return;
     typedef TileList<NG, kMode> Tiles;
     constexpr int NT = Tiles::count;
     constexpr int M = gram_stage_m(NG);
