@@ -33,7 +33,7 @@ def test_distance_range_symmetry_negation_scaling(orc, b):
     assert -1e-12 <= d <= 2.0 + 1e-12                    # Sec. 1: the range of the cosine distance
     assert abs(d - orc.cosine_distance(y, x)) < 1e-14
     assert abs(orc.cosine_distance(x, -y) - (2.0 - d)) < 1e-12
-    assert abs(orc.cosine_distance(f32(4.0) * x, f32(0.125) * y) - d) < 1e-14   # exact rescaling
+    assert abs(orc.cosine_distance(f32(4.0) * x, f32(2.0) * y) - d) < 1e-14   # exact rescaling (upwards: no underflow)
     assert abs(orc.cosine_distance(x, x)) < 1e-12
 
 
