@@ -22,7 +22,7 @@ def orc(oracle):
     return oracle
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(b=batches(min_n=2, max_n=2))
 def test_distance_range_symmetry_negation_scaling(orc, b):
     x, y = b[0], b[1]
@@ -37,7 +37,7 @@ def test_distance_range_symmetry_negation_scaling(orc, b):
     assert abs(orc.cosine_distance(x, x)) < 1e-12
 
 
-@settings(max_examples=150, deadline=None)
+@settings(max_examples=150, deadline=None, derandomize=True)
 @given(b=batches(), tau=st.sampled_from([0.3, 0.9, 0.97, 1.0, 1.05, 1.5]))
 def test_aggregate_invariants(orc, b, tau):
     grads = [np.ascontiguousarray(r) for r in b]
@@ -62,7 +62,7 @@ def test_aggregate_invariants(orc, b, tau):
     np.testing.assert_allclose(dist2, dist[keep], rtol=0, atol=1e-14)
 
 
-@settings(max_examples=100, deadline=None)
+@settings(max_examples=100, deadline=None, derandomize=True)
 @given(b=batches(min_n=2))
 def test_threshold_limits(orc, b):
     grads = [np.ascontiguousarray(r) for r in b]
@@ -75,7 +75,7 @@ def test_threshold_limits(orc, b):
     assert c == 1 and np.array_equal(out, grads[0].astype(np.float64))
 
 
-@settings(max_examples=100, deadline=None)
+@settings(max_examples=100, deadline=None, derandomize=True)
 @given(b=batches(min_n=2, max_n=5, min_p=2))
 def test_pairwise_matches_pairs_and_best_seed_matches_rotations(orc, b):
     grads = [np.ascontiguousarray(r) for r in b]
