@@ -309,6 +309,39 @@ def test_streaming_state_is_resumable(ctx, oracle):
     assert int(count2.item()) == ref[3] and rel_l2(accum2.cpu().numpy(), ref[0]) <= 1e-5
 
 
+def test_tiny_integer_batches_against_exact_arithmetic(ctx):
+    """Small integer vectors, on which Algorithm 1 can be decided without rounding (comparisons of
+    squares of rationals, see test_oracle_pins): the device's mask and count must be the exact
+    ones, including the tie D = tau = 1 of orthogonal vectors, and the mean the exact fraction.
+    Cases whose distance comes within 1e-6 of tau without being that tie are left out (the
+    sequential schedule's running mean is binary32)."""
+    from fractions import Fraction
+    from test_oracle_pins import _exact_filter
+    rng = np.random.default_rng(99)
+    checked = ties = 0
+    for trial in range(300):
+        N, P = int(rng.integers(2, 7)), int(rng.integers(1, 9))
+        rows = rng.integers(-4, 5, size=(N, P)).tolist()
+        tau32 = np.float32(rng.choice([0.5, 0.9, 0.97, 1.0, 1.03, 1.3]))
+        exact = _exact_filter(rows, Fraction(float(tau32)), list(range(N)))
+        if exact is None:
+            continue
+        accepted, mean = exact
+        grads = [torch.tensor(r, dtype=torch.float32).cuda() for r in rows]
+        out, mask, dist, count = gaf.gaf_aggregate(ctx, grads, float(tau32))
+        d = dist.cpu().numpy().astype(np.float64)
+        near = np.abs(d[1:] - float(tau32)) < 1e-6
+        tie = (d[1:] == 1.0) & (float(tau32) == 1.0)
+        if np.any(near & ~tie):
+            continue
+        assert [i for i in range(N) if mask[i].item()] == accepted, (rows, float(tau32), d)
+        assert int(count.item()) == len(accepted)
+        np.testing.assert_allclose(out.cpu().numpy(), [float(m) for m in mean], rtol=2e-6, atol=1e-6)
+        checked += 1
+        ties += int(np.any(tie))
+    assert checked > 200 and ties > 5
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_streaming_long_vectors(ctx, oracle, dtype):
     """From 2^26 elements on a streaming visit is three launches (reduce, decide, update with one
