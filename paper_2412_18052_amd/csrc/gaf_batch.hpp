@@ -82,10 +82,10 @@ enum : int { kSpecNone = 0, kSpecGuess = 1, kSpecVerify = 2, kSpecVerifyCarried 
 // carried form then stores the accept set just computed as the next call's guess. All on the
 // device, so a caller whose gradients sit close to the threshold stops paying for wrong guesses
 // without ever synchronising.
-__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
-                                                    uint8_t *mask, float *cos_dist, int32_t *count,
-                                                    int32_t *accepted_list, int spec = kSpecNone,
-                                                    Prediction *pred = nullptr, int min_count = 0)
+// The body, run by one full wavefront (threadIdx.x = lane).
+__device__ __forceinline__ void filter_body(const double *gram, int N, float tau, State *st, uint8_t *mask,
+                                            float *cos_dist, int32_t *count, int32_t *accepted_list, int spec,
+                                            Prediction *pred, int min_count)
 {
     if (spec == kSpecGuess && pred->backoff > 0) {
         // backing off: the sampling launch did not run either, there is no guess
@@ -138,6 +138,14 @@ __global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, f
             }
         }
     }
+}
+
+__global__ __launch_bounds__(64) void filter_kernel(const double *gram, int N, float tau, State *st,
+                                                    uint8_t *mask, float *cos_dist, int32_t *count,
+                                                    int32_t *accepted_list, int spec = kSpecNone,
+                                                    Prediction *pred = nullptr, int min_count = 0)
+{
+    filter_body(gram, N, tau, st, mask, cos_dist, count, accepted_list, spec, pred, min_count);
 }
 
 // Forgets the record of earlier guesses (a fresh context, or the schedule was set anew).
@@ -402,6 +410,56 @@ __global__ __launch_bounds__(kBlock) void gram_small_finalize_kernel(const doubl
         gram[i * N + j] = s;
         gram[j * N + i] = s;
     }
+}
+
+// Small batches with few partial sums (N (N + 1) / 2 * nb <= kFinalizeFilterMax): the ordered
+// combine of the small-batch Gram kernel's partials and the filter replay in ONE launch of one
+// workgroup -- at these sizes the launches are what a call costs (P = 1e6, N = 4: four launches of
+// 5-6 us; the paper's own N = 2 at P = 11 M: 42-53 us in all). Each pair gets S threads (S = the
+// largest power of two with pairs * S <= 256); thread (pair, slice) adds the partials slice,
+// slice + S, ... in order, then the S slice sums are added by halving (slice k takes slice
+// k + S/2, ...): a fixed tree, but not the one of gram_small_finalize_kernel -- the last bits of
+// the inner products may differ between entry points that take the one route or the other. The
+// matrix goes to LDS for the filter and to `gram` for whoever reads it later.
+constexpr int kFinalizeFilterMax = 8192;
+
+__global__ __launch_bounds__(kBlock) void finalize_filter_kernel(const double *partials, int nb, double *gram,
+                                                                 int N, float tau, State *st, uint8_t *mask,
+                                                                 float *cos_dist, int32_t *count,
+                                                                 int32_t *accepted_list, int spec,
+                                                                 Prediction *pred, int min_count)
+{
+    __shared__ double red[kBlock];
+    __shared__ double g[kSmallMaxN * kSmallMaxN];
+    const int np = N * (N + 1) / 2;
+    int S = 1;
+    while (2 * S * np <= kBlock) S *= 2;
+    const int pair = threadIdx.x / S, slice = threadIdx.x % S;
+    double s = 0.0;
+    if (pair < np)
+        for (int b = slice; b < nb; b += S) s += partials[size_t(pair) * kMaxBlocks + b];
+    red[threadIdx.x] = s;
+    for (int h = S / 2; h >= 1; h /= 2) {
+        __syncthreads();
+        if (pair < np && slice < h) red[threadIdx.x] += red[threadIdx.x + h];
+    }
+    __syncthreads();
+    if (int(threadIdx.x) < np) {
+        const double v = red[threadIdx.x * S];
+        int i = 0, left = threadIdx.x;    // pair index -> (i, j), j >= i, row-major upper triangle
+        while (left >= N - i) {
+            left -= N - i;
+            ++i;
+        }
+        const int j = i + left;
+        g[i * N + j] = v;
+        g[j * N + i] = v;
+        gram[i * N + j] = v;
+        gram[j * N + i] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 64)
+        filter_body(g, N, tau, st, mask, cos_dist, count, accepted_list, spec, pred, min_count);
 }
 
 struct MeanArgs {

@@ -384,10 +384,13 @@ gaf_status gram_small_launch(const SmallGramArgs &g, int nb, hipStream_t s)
 }
 
 // With `mean_out` the launch also writes the mean of ctx->pred's accept set there.
+// `merge_nb` non-null: if the partial sums are few enough for the filter launch to combine them
+// itself (finalize_filter_kernel), the combine launch is left out and *merge_nb receives the
+// number of workgroups whose partials are waiting; otherwise *merge_nb = 0.
 template <typename T, bool kStream>
 gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, hipStream_t s,
                       gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr, size_t chunk_stride = 0,
-                      int carry_n = 0)
+                      int carry_n = 0, int *merge_nb = nullptr)
 {
     if (chunk_stride && (mean_out || P % kSampleChunk)) return GAF_EINVAL;
     SmallGramArgs g{};
@@ -417,6 +420,10 @@ gaf_status gram_small(gaf_ctx *ctx, const void *const *grads, int N, size_t P, h
         }
     }
     if (rc != GAF_OK) return rc;
+    if (merge_nb) {
+        *merge_nb = (N * (N + 1) / 2) * nb <= kFinalizeFilterMax ? nb : 0;
+        if (*merge_nb) return GAF_OK;
+    }
     {
         Timed t(ctx, s, GAF_K_GRAM_FINALIZE);
         gram_small_finalize_kernel<<<N * (N + 1) / 2, kBlock, 0, s>>>(ctx->gram_ws, nb, N, ctx->gram_full);
@@ -472,27 +479,42 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         if (launched() != GAF_OK) return GAF_EHIP;
         ctx->pred_reset = false;
     }
+    // Small batches whose filter launch can combine the Gram kernel's partial sums itself (the
+    // plain call only: the matrix and best-seed forms keep the separate combine, and with it the
+    // bits of gaf_pairwise).
+    const bool may_merge = small && !gram && !opt.best_seed && !opt.dist_matrix;
+    int merge_nb = 0;
     if (speculate && !carried) {
         const size_t cs = spec_chunk_stride(P);
-        gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs)
+        gaf_status rc = small ? gram_small<T, false>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs, 0,
+                                                     may_merge ? &merge_nb : nullptr)
                               : gram_all_pairs<T>(ctx, grads, N, kSpecSample, s, GAF_K_GRAM_SAMPLE, nullptr, cs);
         if (rc != GAF_OK) return rc;
         {
             Timed t(ctx, s, GAF_K_FILTER);
-            filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, &ctx->seed_ws->mask[0][0],
-                                           &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list,
-                                           kSpecGuess, ctx->pred, spec_min_count<T>(N, false));
+            if (merge_nb)
+                finalize_filter_kernel<<<1, kBlock, 0, s>>>(ctx->gram_ws, merge_nb, ctx->gram_full, N, tau, ctx->st,
+                                                            &ctx->seed_ws->mask[0][0], &ctx->seed_ws->dist[0][0],
+                                                            &ctx->pred->count, ctx->pred->list, kSpecGuess,
+                                                            ctx->pred, spec_min_count<T>(N, false));
+            else
+                filter_kernel<<<1, 64, 0, s>>>(ctx->gram_full, N, tau, ctx->st, &ctx->seed_ws->mask[0][0],
+                                               &ctx->seed_ws->dist[0][0], &ctx->pred->count, ctx->pred->list,
+                                               kSpecGuess, ctx->pred, spec_min_count<T>(N, false));
         }
         if (launched() != GAF_OK) return GAF_EHIP;
     }
+    merge_nb = 0;
     if (speculate) {
         const int carry_n = carried ? N : 0;
-        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s, GAF_K_GRAM, out, 0, carry_n)
+        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s, GAF_K_GRAM, out, 0, carry_n,
+                                                             may_merge ? &merge_nb : nullptr)
                                     : gram_all_pairs<T>(ctx, grads, N, P, s, GAF_K_GRAM, out, 0, carry_n);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     } else if (!gram) {
-        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s)
+        const gaf_status rc = small ? gram_small<T, kStream>(ctx, grads, N, P, s, GAF_K_GRAM, nullptr, 0, 0,
+                                                             may_merge ? &merge_nb : nullptr)
                                     : gram_all_pairs<T>(ctx, grads, N, P, s);
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
@@ -509,10 +531,15 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
                                                 opt.best_seed, ctx->accepted);
         }
     } else {
+        const int spec = !speculate ? kSpecNone : carried ? kSpecVerifyCarried : kSpecVerify;
         Timed t(ctx, s, GAF_K_FILTER);
-        filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted,
-                                       !speculate ? kSpecNone : carried ? kSpecVerifyCarried : kSpecVerify,
-                                       ctx->pred, spec_min_count<T>(N, carried));
+        if (merge_nb)
+            finalize_filter_kernel<<<1, kBlock, 0, s>>>(ctx->gram_ws, merge_nb, ctx->gram_full, N, tau, ctx->st, mask,
+                                                        cos_dist, count, ctx->accepted, spec, ctx->pred,
+                                                        spec_min_count<T>(N, carried));
+        else
+            filter_kernel<<<1, 64, 0, s>>>(gram, N, tau, ctx->st, mask, cos_dist, count, ctx->accepted, spec,
+                                           ctx->pred, spec_min_count<T>(N, carried));
     }
     if (launched() != GAF_OK) return GAF_EHIP;
     if (opt.dist_matrix) {
