@@ -61,7 +61,7 @@ def bmin_bytes(w, mask):
     return total
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -92,6 +92,155 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: the library runs on one GPU only (no collectives, no sharding); "
                  "use --gpus 1")
+    return args
+
+
+
+def hbm_roof(alg_bytes, avg_ms):
+    ach = alg_bytes / (avg_ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+            "frac": ach / PEAK_HBM_GBPS}
+
+
+def kernel_rooflines(w, steps, B, per_kernel, records, masks, counts):
+    """Roofline of each streaming kernel from its launch durations in the per-kernel loop:
+    {kernel: (roofline dict, mean launch ms, algorithmic bytes per launch, total ms)}.
+    records: the library's record of guesses after each step of that loop ([] where nothing is
+    guessed); masks, counts: accept mask and count of each of the B batches."""
+    P, N, s = w.P, w.N, w.elem_bytes
+    roofs = {}
+    if "gram" in per_kernel:
+        # one launch reads every gradient once
+        dur = per_kernel["gram"]
+        avg_ms = sum(dur) / len(dur)
+        alg_bytes = float(N * s * P)
+        if records:                 # launches that also wrote the mean of their guess
+            assert len(dur) == len(records)
+            alg_bytes += 4.0 * P * sum(r["write"] for r in records) / len(records)
+        r = hbm_roof(alg_bytes, avg_ms)
+        if N <= 8:
+            # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
+            flops = 2.0 * (N * (N + 1) // 2) * P
+            frac2 = flops / (avg_ms * 1e-3) / 1e12 / PEAK_VALU_F64_TFLOPS
+            if frac2 > r["frac"]:
+                r = {"bound": "alu", "achieved": flops / (avg_ms * 1e-3) / 1e12,
+                     "peak": PEAK_VALU_F64_TFLOPS, "unit": "TFLOP/s", "frac": frac2, "hbm_frac": r["frac"]}
+            else:
+                r["alu_frac"] = frac2
+        else:
+            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups. binary32 rows in
+            # three or four groups are multiplied through a three-way bfloat16 split (six bf16 MFMAs
+            # per product), everything else in its own type.
+            ng = (N + 15) // 16
+            flops = 2.0 * (ng * (ng + 1) // 2) * 256 * P
+            peak_tf = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
+            if w.dtype == "f32" and ng >= 3:
+                flops *= 6
+                peak_tf = PEAK_MFMA_BF16_TFLOPS
+            mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / peak_tf
+            if mfma_frac > r["frac"]:
+                r = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": peak_tf,
+                     "unit": "TFLOP/s", "frac": mfma_frac, "hbm_frac": r["frac"]}
+            else:
+                r["mfma_frac"] = mfma_frac
+        roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
+    if "mean" in per_kernel:
+        # accepted gradients read once, result written once; a launch that finds the result in
+        # place (right guess) returns at once and is left out
+        dur = per_kernel["mean"]
+        assert len(dur) == steps
+        live = [k for k in range(steps) if not (records and records[k]["valid"])]
+        if live:
+            avg_ms = sum(dur[k] for k in live) / len(live)
+            alg_bytes = sum(float(counts[k % B] * s * P + 4 * P) for k in live) / len(live)
+            roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur[k] for k in live))
+    if "reduce" in per_kernel:
+        # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
+        # gradient i - 1 if that one was accepted; a streaming reduce never stores.
+        if w.mode == "step":
+            # the launch for the seed returns at once (nothing to compare with): not counted
+            per_launch = ([None] + [(4 + s) * P] * (N - 1)) * steps
+        else:
+            per_launch = [(4 + s) * P + (4 * P if masks[k % B][i - 1] else 0)
+                          for k in range(steps) for i in range(2, N)]
+        dur = per_kernel["reduce"]
+        assert len(dur) == len(per_launch), (len(dur), len(per_launch))
+        dur = [d for k, d in enumerate(dur) if per_launch[k] is not None]
+        alg = sum(b for b in per_launch if b is not None)
+        avg_ms = sum(dur) / max(1, len(dur))
+        alg_bytes = alg / max(1, len(dur))
+        roofs["reduce"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
+    return roofs
+
+
+def measure_ceilings(gaf, torch):
+    """What this GPU's memory system delivers to the simplest kernels of the library, measured now:
+    a read-only pass (inner products of two binary32 vectors of 2^28 elements: 2 GiB read) and a
+    plain copy (a single-gradient batch: 1 GiB read, 1 GiB written)."""
+    try:
+        E = 1 << 28
+        a_c = torch.ones(E, dtype=torch.float32, device="cuda")
+        b_c = torch.full((E,), 0.5, dtype=torch.float32, device="cuda")
+        cal = gaf.gaf_create(max_P=E, max_N=2)
+        o_c = gaf.gaf_aggregate(cal, [a_c], 1.0)
+        d_c = gaf.gaf_pairwise(cal, [a_c, b_c])
+        torch.cuda.synchronize()
+        gaf.gaf_profile_begin(cal, 256)
+        for _ in range(5):
+            gaf.gaf_aggregate(cal, [a_c], 1.0, *o_c)
+            gaf.gaf_pairwise(cal, [a_c, b_c], d_c)
+        kt = {}
+        for name, ms in gaf.gaf_profile_end(cal, 256):
+            kt.setdefault(name, []).append(ms)
+        gaf.gaf_destroy(cal)
+        return {"read_only": 2 * 4 * E / (min(kt["gram"]) * 1e-3) / 1e9,
+                "copy": 2 * 4 * E / (min(kt["update"]) * 1e-3) / 1e9, "unit": "GB/s",
+                "how": "best of 5 launches each: inner products of two 2^28-element binary32 vectors "
+                       "(read-only), single-gradient batch of one such vector (copy)"}
+    except (torch.OutOfMemoryError, KeyError) as e:      # the workload left no room, or a kernel was renamed
+        return {"error": repr(e)}
+
+
+def cpu_baseline(w, grads, seed, cpu_seconds, wl, np):
+    """The oracle, as it stands, on a bounded sample of the same workload: all N micro-gradients,
+    the first Ps coordinates of each, Ps sized for about cpu_seconds of work."""
+    from oracle import gaf_oracle
+    P, N = w.P, w.N
+    cores = gaf_oracle.num_threads()
+    rate_guess = 1.2e8 * cores          # element visits per second, refined by a probe
+    probe = min(P, 1 << 20)
+    host = [wl.to_host_array(g[:probe]) for g in grads]
+    tp = time.perf_counter()
+    gaf_oracle.aggregate(host, np.float32(w.tau))
+    tp = time.perf_counter() - tp
+    rate_guess = max(rate_guess, N * probe / max(tp, 1e-4))
+    Ps = int(min(P, max(probe, cpu_seconds * rate_guess / N)))
+    if w.mode == "pairwise":
+        Ps = int(min(P, max(1 << 16, Ps // 24)))   # the pair loop costs ~N/2 more passes
+    host = [wl.to_host_array(g[:Ps]) for g in grads]
+    tc = time.perf_counter()
+    if w.mode == "pairwise":
+        gaf_oracle.pairwise(host)
+    if w.mode == "step":
+        acc64 = np.empty(Ps, dtype=np.float64)
+        cnt, o_mask = 0, []
+        for h in host:
+            _, a_i, cnt = gaf_oracle.step(acc64, cnt, h, np.float32(w.tau))
+            o_mask.append(a_i)
+    else:
+        _, o_mask, _, _ = gaf_oracle.aggregate(host, np.float32(w.tau))
+    tc = time.perf_counter() - tc
+    ws = wl.spec(w.name, seed, P=Ps, N=N)
+    cpu_bytes = bmin_bytes(ws, list(o_mask))
+    return {"value": cpu_bytes / tc / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "seconds": tc, "micro_gradients_per_s": N / tc * (Ps / P),
+            "sample": "all %d micro-gradients, first %d of %d coordinates each "
+                      "(%.3g of the workload); micro_gradients_per_s is scaled to full length"
+                      % (N, Ps, P, Ps / P)}
+
+
+def main():
+    args = parse_args()
 
     import numpy as np
     import torch
@@ -215,74 +364,7 @@ def main():
         per_kernel.setdefault(name, []).append(ms)
     launches_per_step = len(times) // args.steps
 
-    # algorithmic bytes (and MFMA flops) per launch of each streaming kernel
-    def hbm_roof(alg_bytes, avg_ms):
-        ach = alg_bytes / (avg_ms * 1e-3) / 1e9
-        return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBPS}
-
-    roofs = {}
-    if "gram" in per_kernel:
-        # one launch reads every gradient once
-        dur = per_kernel["gram"]
-        avg_ms = sum(dur) / len(dur)
-        alg_bytes = float(N * s * P)
-        if records:                 # launches that also wrote the mean of their guess
-            assert len(dur) == len(records)
-            alg_bytes += 4.0 * P * sum(r["write"] for r in records) / len(records)
-        r = hbm_roof(alg_bytes, avg_ms)
-        if N <= 8:
-            # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
-            flops = 2.0 * (N * (N + 1) // 2) * P
-            frac2 = flops / (avg_ms * 1e-3) / 1e12 / PEAK_VALU_F64_TFLOPS
-            if frac2 > r["frac"]:
-                r = {"bound": "alu", "achieved": flops / (avg_ms * 1e-3) / 1e12,
-                     "peak": PEAK_VALU_F64_TFLOPS, "unit": "TFLOP/s", "frac": frac2, "hbm_frac": r["frac"]}
-            else:
-                r["alu_frac"] = frac2
-        else:
-            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups. binary32 rows in
-            # three or four groups are multiplied through a three-way bfloat16 split (six bf16 MFMAs
-            # per product), everything else in its own type.
-            ng = (N + 15) // 16
-            flops = 2.0 * (ng * (ng + 1) // 2) * 256 * P
-            peak_tf = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
-            if w.dtype == "f32" and ng >= 3:
-                flops *= 6
-                peak_tf = PEAK_MFMA_BF16_TFLOPS
-            mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / peak_tf
-            if mfma_frac > r["frac"]:
-                r = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": peak_tf,
-                     "unit": "TFLOP/s", "frac": mfma_frac, "hbm_frac": r["frac"]}
-            else:
-                r["mfma_frac"] = mfma_frac
-        roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
-    if "mean" in per_kernel:
-        # accepted gradients read once, result written once; a launch that finds the result in
-        # place (right guess) returns at once and is left out
-        dur = per_kernel["mean"]
-        assert len(dur) == args.steps
-        live = [k for k in range(args.steps) if not (records and records[k]["valid"])]
-        if live:
-            avg_ms = sum(dur[k] for k in live) / len(live)
-            alg_bytes = sum(float(counts[k % B] * s * P + 4 * P) for k in live) / len(live)
-            roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur[k] for k in live))
-    if "reduce" in per_kernel:
-        # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
-        # gradient i - 1 if that one was accepted; a streaming reduce never stores.
-        if w.mode == "step":
-            # the launch for the seed returns at once (nothing to compare with): not counted
-            per_launch = ([None] + [(4 + s) * P] * (N - 1)) * args.steps
-        else:
-            per_launch = [(4 + s) * P + (4 * P if masks[k % B][i - 1] else 0)
-                          for k in range(args.steps) for i in range(2, N)]
-        dur = per_kernel["reduce"]
-        assert len(dur) == len(per_launch), (len(dur), len(per_launch))
-        dur = [d for k, d in enumerate(dur) if per_launch[k] is not None]
-        alg = sum(b for b in per_launch if b is not None)
-        avg_ms = sum(dur) / max(1, len(dur))
-        alg_bytes = alg / max(1, len(dur))
-        roofs["reduce"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
+    roofs = kernel_rooflines(w, args.steps, B, per_kernel, records, masks, counts)
     dom = max(roofs, key=lambda k: roofs[k][3])      # the kernel the step spends most time in
     roof, avg_ms, alg_bytes, _ = roofs[dom]
     roof["kernel"] = dom
@@ -341,76 +423,21 @@ def main():
         gaf.gaf_set_schedule(ctx, args.schedule)
         state["schedule"] = args.schedule
 
-    # ---- what this GPU's memory system delivers to the simplest kernels of the library, measured
-    # now: a read-only pass (inner products of two binary32 vectors of 2^28 elements: 2 GiB read)
-    # and a plain copy (a single-gradient batch: 1 GiB read, 1 GiB written). The dominant kernel's
-    # rate is also reported as a fraction of whichever of the two matches its read/write mix.
+    # ---- the memory system's own ceilings; the dominant kernel's rate is also reported as a fraction
+    # of whichever of the two matches its read/write mix
     ceilings = None
     if not args.only_profile_loop:
-        try:
-            E = 1 << 28
-            a_c = torch.ones(E, dtype=torch.float32, device="cuda")
-            b_c = torch.full((E,), 0.5, dtype=torch.float32, device="cuda")
-            cal = gaf.gaf_create(max_P=E, max_N=2)
-            o_c = gaf.gaf_aggregate(cal, [a_c], 1.0)
-            d_c = gaf.gaf_pairwise(cal, [a_c, b_c])
-            torch.cuda.synchronize()
-            gaf.gaf_profile_begin(cal, 256)
-            for _ in range(5):
-                gaf.gaf_aggregate(cal, [a_c], 1.0, *o_c)
-                gaf.gaf_pairwise(cal, [a_c, b_c], d_c)
-            kt = {}
-            for name, ms in gaf.gaf_profile_end(cal, 256):
-                kt.setdefault(name, []).append(ms)
-            ceilings = {"read_only": 2 * 4 * E / (min(kt["gram"]) * 1e-3) / 1e9,
-                        "copy": 2 * 4 * E / (min(kt["update"]) * 1e-3) / 1e9, "unit": "GB/s",
-                        "how": "best of 5 launches each: inner products of two 2^28-element binary32 vectors "
-                               "(read-only), single-gradient batch of one such vector (copy)"}
+        ceilings = measure_ceilings(gaf, torch)
+        if "error" not in ceilings:
             writes = ((dom == "gram" and any(r["write"] for r in records)) or dom == "mean" or
                       (dom == "reduce" and w.mode != "step"))
             roof["frac_of_measured_ceiling"] = (roof["achieved"] / ceilings["copy" if writes else "read_only"]
                                                 if roof["bound"] == "hbm" else None)
-            gaf.gaf_destroy(cal)
-            del a_c, b_c, o_c, d_c
-        except (torch.OutOfMemoryError, KeyError) as e:      # the workload left no room, or a kernel was renamed
-            ceilings = {"error": repr(e)}
 
-    # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
+    # ---- CPU baseline ----
     cpu = None
     if args.cpu_seconds > 0 and not args.only_profile_loop:
-        from oracle import gaf_oracle
-        cores = gaf_oracle.num_threads()
-        # sample: all N micro-gradients, the first Ps coordinates of each
-        rate_guess = 1.2e8 * cores          # element visits per second, refined by a probe
-        probe = min(P, 1 << 20)
-        host = [wl.to_host_array(g[:probe]) for g in grads]
-        tp = time.perf_counter()
-        gaf_oracle.aggregate(host, np.float32(w.tau))
-        tp = time.perf_counter() - tp
-        rate_guess = max(rate_guess, N * probe / max(tp, 1e-4))
-        Ps = int(min(P, max(probe, args.cpu_seconds * rate_guess / N)))
-        if w.mode == "pairwise":
-            Ps = int(min(P, max(1 << 16, Ps // 24)))   # the pair loop costs ~N/2 more passes
-        host = [wl.to_host_array(g[:Ps]) for g in grads]
-        tc = time.perf_counter()
-        if w.mode == "pairwise":
-            gaf_oracle.pairwise(host)
-        if w.mode == "step":
-            acc64 = np.empty(Ps, dtype=np.float64)
-            cnt, o_mask = 0, []
-            for h in host:
-                _, a_i, cnt = gaf_oracle.step(acc64, cnt, h, np.float32(w.tau))
-                o_mask.append(a_i)
-        else:
-            _, o_mask, _, _ = gaf_oracle.aggregate(host, np.float32(w.tau))
-        tc = time.perf_counter() - tc
-        ws = wl.spec(w.name, args.seed, P=Ps, N=N)
-        cpu_bytes = bmin_bytes(ws, list(o_mask))
-        cpu = {"value": cpu_bytes / tc / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-               "seconds": tc, "micro_gradients_per_s": N / tc * (Ps / P),
-               "sample": "all %d micro-gradients, first %d of %d coordinates each "
-                         "(%.3g of the workload); micro_gradients_per_s is scaled to full length"
-                         % (N, Ps, P, Ps / P)}
+        cpu = cpu_baseline(w, grads, args.seed, args.cpu_seconds, wl, np)
 
     line = {
         "metric": "gaf_filter_average_effective_hbm_gbps",
