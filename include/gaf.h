@@ -197,7 +197,8 @@ gaf_status gaf_fused_mean_record(gaf_ctx *ctx, int32_t record[4]);
  *
  * Two kernels: the distance reduction, then decision and conditional update in
  * one launch (every workgroup re-derives the decision from the partial sums; a
- * rejected g_i costs no further memory traffic).
+ * rejected g_i costs no further memory traffic). From P = 2^26 on: three (the
+ * decision gets a launch of its own and the update runs one workgroup per tile).
  */
 gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
                     gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
