@@ -241,6 +241,9 @@ gaf_status gaf_aggregate_with_gram(gaf_ctx *ctx, const void *const *grads, int N
  *   D     DEVICE, N*N binary32 distances as in gaf_pairwise.
  *   gram  DEVICE, N*N binary64 inner products, may be NULL.
  * 1 <= N <= 64 (GAF_EUNSUPPORTED beyond); other arguments as in gaf_aggregate.
+ * D and gram are bit for bit those of gaf_pairwise. For N <= 8 the plain
+ * gaf_aggregate may add its partial inner products in another (equally fixed)
+ * order, so its cos_dist can differ from this call's in the last bit.
  */
 gaf_status gaf_aggregate_with_matrix(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
                                      gaf_dtype dt, float tau, float *out, uint8_t *accept_mask,
