@@ -29,17 +29,34 @@ using bf16_t = uint16_t;  // storage type of a bfloat16 element
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
+// Every gradient and aggregate lives in global memory, but a pointer that reaches a kernel by
+// way of a table in LDS is "generic" to the compiler, and an access through a generic pointer
+// becomes a flat_ instruction: it counts against the LDS counter as well as the vector-memory
+// one, so that every wait for an LDS read also waits for it and the two can no longer be
+// pipelined apart. The loaders therefore say where the data is.
+#define GAF_GLOBAL __attribute__((address_space(1)))
+template <typename V>
+__device__ __forceinline__ const GAF_GLOBAL V *as_global(const void *p)
+{
+    return (const GAF_GLOBAL V *)p;
+}
+template <typename V>
+__device__ __forceinline__ GAF_GLOBAL V *as_global(void *p)
+{
+    return (GAF_GLOBAL V *)p;
+}
+
 template <bool kStream = false>
 __device__ __forceinline__ float4 load4(const float *p, size_t idx)
 {
-    const f32x4_t *q = reinterpret_cast<const f32x4_t *>(p + idx);   // 16-byte load
+    const GAF_GLOBAL f32x4_t *q = as_global<f32x4_t>(p + idx);   // 16-byte load
     const f32x4_t v = kStream ? __builtin_nontemporal_load(q) : *q;
     return make_float4(v.x, v.y, v.z, v.w);
 }
 template <bool kStream = false>
 __device__ __forceinline__ float4 load4(const bf16_t *p, size_t idx)
 {
-    const u32x2_t *q = reinterpret_cast<const u32x2_t *>(p + idx);   // 8-byte load
+    const GAF_GLOBAL u32x2_t *q = as_global<u32x2_t>(p + idx);   // 8-byte load
     const u32x2_t r = kStream ? __builtin_nontemporal_load(q) : *q;
     return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xffff0000u),
                        __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xffff0000u));
@@ -49,6 +66,32 @@ __device__ __forceinline__ float load1(const bf16_t *p, size_t idx)
 {
     return __uint_as_float(static_cast<uint32_t>(p[idx]) << 16);
 }
+
+// ---- write windows -----------------------------------------------------------
+// A pass that mostly reads but also writes pays far more for its written bytes than a pass that
+// only writes: measured on vectors of a GiB, one 1 KB store per 8 KB of loads costs 0.57 ms per
+// GiB written against 0.22 ms per GiB for stores alone, wherever in the loop the store is issued,
+// in bursts or not, temporal or not -- the memory turns around between reading and writing for
+// every small group of writes. What does help is making the WHOLE chip write at the same time.
+// The constant 100 MHz clock (s_memrealtime) reads the same in every compute unit, so it can
+// serve as the conductor without any communication: time is cut into periods of 2^k ticks whose
+// first `win` ticks are the write window. A workgroup keeps its results on chip, writes them out
+// when it finds the window open, and then idles until the window closes, so that for a few
+// microseconds the memory sees (nearly) nothing but writes and for the rest of the period nothing
+// but reads (measured on the same mix: 1.81 -> 1.45 ms, 6.7 TB/s in total).
+// Results never depend on it: the same values go to the same addresses, only later. Waiting is
+// bounded by the clock and, should the clock not move, by a spin limit.
+struct WriteGate {
+    unsigned mask, win;      // period - 1 and window length in 10 ns ticks; win == 0: never open
+    __device__ __forceinline__ bool open() const
+    {
+        return win != 0 && (unsigned(__builtin_amdgcn_s_memrealtime()) & mask) < win;
+    }
+    __device__ __forceinline__ void wait_closed() const
+    {
+        for (int spin = 0; spin < 4096 && open(); ++spin) __builtin_amdgcn_s_sleep(4);
+    }
+};
 
 // ---- wavefront reduction through DPP ---------------------------------------
 // Moves a binary64 value between lanes with one DPP control word (two 32-bit

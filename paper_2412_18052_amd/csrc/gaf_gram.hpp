@@ -25,6 +25,8 @@
 // MFMAs of stage k. Tiles accumulate in binary32 inside the matrix core and are
 // flushed into binary64 registers every kGramFlush stages.
 #pragma once
+#include <type_traits>
+
 #include "gaf_device.hpp"
 
 namespace gaf {
@@ -67,9 +69,12 @@ struct TileList {
     }
 };
 
-// Stage width in units of 256 bytes per row, by number of row groups: keeps
-// 3-4 KB of loads in flight per wavefront whatever the row count.
-__host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 8 : ng == 2 ? 4 : 2; }
+// Stage width in units of 256 bytes per row, by number of row groups: 16 KB per stage with one
+// or two groups, 32 KB with three or four, i.e. 32-64 KB of loads in flight per compute unit.
+// (Measured with plain streaming loops: 16-32 KB in flight per compute unit already saturate the
+// memory system; beyond 64 KB the queues in front of it only get longer.) The width is the same
+// for every variant of a group count, so that all of them add the columns in the same order.
+__host__ __device__ constexpr int gram_stage_m(int ng) { return ng == 1 ? 4 : 2; }
 
 // An accept set guessed before the full inner products are known: which gradients
 // Algorithm 1 will probably accept, in visiting order, and what is done with the guess.
@@ -116,17 +121,20 @@ struct GramArgs {
     // an ordinary launch has chunk_shift = 62 (one run that never ends) and chunk_stride = 0.
     int chunk_shift;
     size_t chunk_stride;
+    // kMean only: write windows (see WriteGate). gate_mask = period - 1 in ticks of the constant
+    // 100 MHz clock (period a power of two), gate_win = length of the window in ticks; 0 = no windows.
+    unsigned gate_mask, gate_win;
 };
 
 // 16 bytes of a row starting at element p, element-wise and zero past the end.
-__device__ __forceinline__ u32x4_t gram_load_guarded(const float *row, size_t p, size_t P)
+__device__ __forceinline__ u32x4_t gram_load_guarded(const GAF_GLOBAL float *row, size_t p, size_t P)
 {
     u32x4_t v;
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] = p + e < P ? __float_as_uint(row[p + e]) : 0u;
     return v;
 }
-__device__ __forceinline__ u32x4_t gram_load_guarded(const bf16_t *row, size_t p, size_t P)
+__device__ __forceinline__ u32x4_t gram_load_guarded(const GAF_GLOBAL bf16_t *row, size_t p, size_t P)
 {
     u32x4_t v;
 #pragma unroll
@@ -187,23 +195,26 @@ __device__ __forceinline__ void mma_bf16(const bf16x8_t &x, const bf16x8_t &y, f
 // (three or four row groups); with one or two groups the kernel is memory bound
 // either way and the split would only add vector-ALU work.
 //
-// kHalves = 2: a workgroup is two halves of 256 threads; each half is one "virtual workgroup"
-// with its own stage buffers, stages and partial tiles (the decomposition of the work, and so
-// every bit of the result, is the same as with kHalves = 1 and twice the grid) and the halves
-// share nothing but the barriers. That is the point: two independent 256-thread workgroups on
-// one compute unit do not progress evenly -- measured with the writing bf16 kernel, the one
-// dispatched first ends 15 % before the other, which then runs alone at half the unit's
-// capacity; halves of one workgroup are held together by the barrier of every stage (-4.5 % on
-// that kernel; the read-only and the binary32 kernels lose 3-6 % to the lockstep and keep
-// kHalves = 1).
-template <typename T, int NG, int kMode, bool kMean = false, int kHalves = 1,
-          bool kSplit = (sizeof(T) == 4 && NG >= 3)>
-__global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
+constexpr int kLdsPerBlock = 79 * 1024;   // bytes of LDS a workgroup may use: two workgroups per compute unit (160 KB)
+
+// Geometry of a writing (kMean) kernel's LDS, by element size and number of row groups: words per
+// stage buffer (16 NG rows and the zero row, each padded), bytes of one stage's piece of the mean,
+// and how many such pieces the ring behind the two stage buffers holds.
+__host__ __device__ constexpr int gram_mean_stage_words(int ng) { return (16 * ng + 1) * (64 * gram_stage_m(ng) + kGramPad); }
+__host__ __device__ constexpr int gram_piece_bytes(int elem_bytes, int ng) { return 256 * gram_stage_m(ng) / elem_bytes * 4; }
+__host__ __device__ constexpr int gram_hold_stages_for(int elem_bytes, int ng)
 {
-    static_assert(kHalves == 1 || kHalves == 2, "one or two virtual workgroups per workgroup");
-    const int half = kHalves == 1 ? 0 : int(threadIdx.x) / kBlock;
-    const int tid = kHalves == 1 ? int(threadIdx.x) : int(threadIdx.x) % kBlock;
-    const size_t vblock = size_t(blockIdx.x) * kHalves + half;       // virtual workgroup
+    const int n = (kLdsPerBlock - 2 * gram_mean_stage_words(ng) * 4) / gram_piece_bytes(elem_bytes, ng);
+    return n < 64 ? n : 64;
+}
+template <typename T>
+constexpr int gram_hold_stages(int ng) { return gram_hold_stages_for(int(sizeof(T)), ng); }
+
+template <typename T, int NG, int kMode, bool kMean = false, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
+{
+    const int tid = int(threadIdx.x);
+    const size_t vblock = blockIdx.x;
     // a sampling launch has nothing to do while a backoff runs: no guess will be written
     if (a.chunk_stride != 0 && a.pred->backoff > 0) return;
     typedef TileList<NG, kMode> Tiles;
@@ -211,16 +222,28 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
     constexpr int M = gram_stage_m(NG);
     constexpr int kRows = 16 * NG;
     constexpr int kRowWords = 64 * M + kGramPad;            // LDS words per row of a stage
-    constexpr int kStageWords = kRows * kRowWords;
+    // kMean: one more row per stage buffer, all zeros, stands in for "no gradient" (see mean_piece)
+    constexpr int kStageWords = (kRows + (kMean ? 1 : 0)) * kRowWords;
     constexpr int kElem16 = 16 / sizeof(T);                 // elements per 16-byte piece
     constexpr size_t kStageElems = size_t(256) * M / sizeof(T);   // elements of each row per stage
     constexpr int kInner = sizeof(T) == 4 ? 4 : 1;          // MFMAs per 16-byte register
     static_assert(2 * kStageWords * 4 >= NT * kGramTile * 8, "stage buffers are reused for the final combine");
 
-    __shared__ __attribute__((aligned(16))) uint32_t stage_all[kHalves][2 * kStageWords];
+    // kMean: the first kQuads threads each own four consecutive columns of a stage (16-byte stores;
+    // 8-byte ones by twice the threads measured 2 % slower), and a ring of finished pieces of the
+    // mean (one piece = the stage's kStageElems binary32 results) waits in LDS for the next write
+    // window: whatever a workgroup's share of the LDS (two workgroups per compute unit) leaves
+    // after the stage buffers.
+    constexpr int kQuads = int(kStageElems) / 4;
+    static_assert(kQuads <= kBlock, "at most one quad of a stage per thread");
+    constexpr int kPieceBytes = int(kStageElems) * 4;
+    constexpr int kHoldStages = kMean ? gram_hold_stages<T>(NG) : 0;
+    static_assert(!kMean || (kHoldStages >= 8 && kStageWords == gram_mean_stage_words(NG) && kPieceBytes == gram_piece_bytes(sizeof(T), NG)),
+                  "ring geometry");
+    constexpr int kHoldWords = kHoldStages * kPieceBytes / 4;
+    __shared__ __attribute__((aligned(16))) uint32_t stage[2 * kStageWords + kHoldWords];
     __shared__ const void *row_table[kGramRows];
-    __shared__ int32_t pred_rows[kGramRows];
-    uint32_t *const stage = stage_all[half];
+    __shared__ int gate_flag[2];
 
     const int lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, sub = lane >> 4;
@@ -234,23 +257,34 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
             if (int(threadIdx.x) == k) p = a.rows[k];
         row_table[threadIdx.x] = p;
     }
+    // kMean: LDS word offset, within a stage buffer, of the k-th gradient of the guessed accept set
+    // (visiting order); entries past the guess point at the zero row. Uniform, so they live in
+    // scalar registers and the LDS reads of mean_piece depend on nothing but the stage buffer.
     int c_pred = 0;
     bool write_mean = false;
+    int pred_word[kMean ? kRows : 1];
     if (kMean) {
         c_pred = a.pred->count;
         write_mean = a.carry_n ? carried_guess_writes(a.pred, a.carry_n, a.min_count) : a.pred->write != 0;
         if (!write_mean) c_pred = 0;
-        if (int(threadIdx.x) < c_pred) pred_rows[threadIdx.x] = a.pred->list[threadIdx.x];
+        if (c_pred > kRows) c_pred = kRows;
+#pragma unroll
+        for (int k = 0; k < kRows; ++k) {
+            const int r = k < c_pred ? a.pred->list[k] : -1;
+            pred_word[k] = __builtin_amdgcn_readfirstlane((r >= 0 && r < kRows ? r : kRows) * kRowWords);
+        }
+        for (int w = tid; w < kRowWords; w += kBlock)
+            stage[kRows * kRowWords + w] = stage[kStageWords + kRows * kRowWords + w] = 0u;
     }
     __syncthreads();
 
     // loading role: this wavefront owns rows [4 NG wave, 4 NG (wave+1)); lane = (row sub, 16-byte piece l16)
-    const T *lrow[NG];
+    const GAF_GLOBAL T *lrow[NG];
     int lword[NG];
 #pragma unroll
     for (int j = 0; j < NG; ++j) {
         const int rr = 4 * NG * wave + 4 * j + sub;
-        lrow[j] = static_cast<const T *>(row_table[rr]);
+        lrow[j] = as_global<T>(row_table[rr]);
         lword[j] = rr * kRowWords + l16 * 4;
     }
     // computing role: this wavefront owns columns [16 M wave, 16 M (wave+1)) words of every row;
@@ -259,7 +293,7 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
 
     const size_t P = a.P;
     const size_t nfull = P / kStageElems;
-    const size_t G = size_t(gridDim.x) * kHalves;               // virtual workgroups
+    const size_t G = gridDim.x;
 
     floatx4 acc[NT];
     double tot[NT][4];
@@ -283,7 +317,7 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
 #pragma unroll
             for (int m = 0; m < M; ++m)
                 pre[j][m] = __builtin_nontemporal_load(
-                    reinterpret_cast<const u32x4_t *>(lrow[j] + e0 + size_t(m) * 16 * kElem16));
+                    reinterpret_cast<const GAF_GLOBAL u32x4_t *>(lrow[j] + e0 + size_t(m) * 16 * kElem16));
     };
     auto gload_guarded = [&](size_t s) {
         const size_t e0 = s * kStageElems + size_t(l16) * kElem16;
@@ -339,40 +373,68 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
                 for (int t = 0; t < NT; ++t) gram_mma<T>(x[Tiles::ga(t)], x[Tiles::gb(t)], acc[t], e);
         }
     };
-    // Eq. 5 over the predicted accept set for the stage in buffer `buf` (stage index s):
-    // each thread owns 4 consecutive columns, sums the predicted rows in visiting order.
-    auto mean_stage = [&](int buf, size_t s) {
-        constexpr int kQuads = int(kStageElems / 4);
-        const float inv_c = 1.0f / (float)c_pred;
-        const size_t e_base = s * kStageElems;
-        for (int q = tid; q < kQuads; q += kBlock) {
-            f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
-            for (int k = 0; k < c_pred; ++k) {
-                const uint32_t *src = &stage[buf * kStageWords + pred_rows[k] * kRowWords];
+    // Eq. 5 over the guessed accept set for the stage in buffer `buf`: a thread adds, for each of
+    // its four columns, the guessed rows in visiting order. All 16 NG reads are issued at once
+    // (their addresses are scalar offsets plus the thread's columns); rows past the guess read the
+    // zero row, and adding +0 changes no bit of a sum that started from +0.
+    const float inv_c = 1.0f / (float)(c_pred > 0 ? c_pred : 1);
+    auto mean_piece = [&](int buf) {
+        f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+        if (tid < kQuads) {
+            const uint32_t *src = &stage[buf * kStageWords + (sizeof(T) == 4 ? 4 : 2) * tid];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                if (16 * g >= c_pred) break;          // uniform
                 if (sizeof(T) == 4) {
-                    const u32x4_t w = *reinterpret_cast<const u32x4_t *>(src + 4 * q);
-                    sum.x += __uint_as_float(w.x);
-                    sum.y += __uint_as_float(w.y);
-                    sum.z += __uint_as_float(w.z);
-                    sum.w += __uint_as_float(w.w);
+                    u32x4_t w[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32x4_t *>(src + pred_word[16 * g + k]);
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        sum.x += __uint_as_float(w[k].x);
+                        sum.y += __uint_as_float(w[k].y);
+                        sum.z += __uint_as_float(w[k].z);
+                        sum.w += __uint_as_float(w[k].w);
+                    }
                 } else {
-                    const u32x2_t w = *reinterpret_cast<const u32x2_t *>(src + 2 * q);
-                    sum.x += __uint_as_float(w.x << 16);
-                    sum.y += __uint_as_float(w.x & 0xffff0000u);
-                    sum.z += __uint_as_float(w.y << 16);
-                    sum.w += __uint_as_float(w.y & 0xffff0000u);
+                    u32x2_t w[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32x2_t *>(src + pred_word[16 * g + k]);
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        sum.x += __uint_as_float(w[k].x << 16);
+                        sum.y += __uint_as_float(w[k].x & 0xffff0000u);
+                        sum.z += __uint_as_float(w[k].y << 16);
+                        sum.w += __uint_as_float(w[k].y & 0xffff0000u);
+                    }
                 }
             }
-            const f32x4_t o = {sum.x * inv_c, sum.y * inv_c, sum.z * inv_c, sum.w * inv_c};
-            const size_t idx = e_base + size_t(q) * 4;
-            if (idx + 4 <= P) {
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t *>(a.out + idx));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (idx + e < P) a.out[idx + e] = o[e];
-            }
         }
+        return f32x4_t{sum.x * inv_c, sum.y * inv_c, sum.z * inv_c, sum.w * inv_c};
+    };
+    // The mean of full stage s: one 16-byte store per thread, 4 KB or less, contiguous.
+    GAF_GLOBAL float *const mean_out = as_global<float>(a.out);
+    auto mean_store = [&](const f32x4_t &o, size_t s) {
+        if (tid < kQuads)
+            __builtin_nontemporal_store(o, reinterpret_cast<GAF_GLOBAL f32x4_t *>(mean_out + s * kStageElems + size_t(tid) * 4));
+    };
+    // ragged last stage: element-wise guarded
+    auto mean_store_guarded = [&](const f32x4_t &o, size_t s) {
+        const size_t idx = s * kStageElems + size_t(tid) * 4;
+        if (tid < kQuads)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (idx + e < P) mean_out[idx + e] = o[e];
+    };
+    // Pieces of the mean wait in the LDS ring (each thread reads back only what it wrote itself).
+    f32x4_t *const hold = reinterpret_cast<f32x4_t *>(stage + 2 * kStageWords);
+    auto hold_put = [&](int slot, const f32x4_t &o) {
+        if (tid < kQuads) hold[slot * kQuads + tid] = o;
+    };
+    // writes out the `n` held pieces, which belong to stages s0, s0 + G, ...
+    auto hold_flush = [&](int n, size_t s0) {
+        if (tid < kQuads)
+            for (int j = 0; j < n; ++j) mean_store(hold[j * kQuads + tid], s0 + size_t(j) * G);
     };
     auto flush = [&]() {
 #pragma unroll
@@ -384,18 +446,37 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
             }
     };
 
+    // This workgroup takes stages blockIdx.x, blockIdx.x + G, ...: n_mine of them. All but the last
+    // have a successor to prefetch; they run as a loop without a condition around its loads, so
+    // that the compiler can count them: the wait before the LDS stores then covers the prefetching
+    // loads and nothing younger.
+    const size_t n_mine = nfull > vblock ? (nfull - vblock + G - 1) / G : 0;
+    const size_t n_steady = n_mine > 0 ? n_mine - 1 : 0;
     int buf = 0, since_flush = 0;
-    if constexpr (kHalves == 1) {
-        // stages blockIdx.x, blockIdx.x + G, ...
-        size_t s = blockIdx.x;
-        if (s < nfull) {
-            gload(s);
+    auto run = [&](auto with_mean) {
+        constexpr bool kWrite = kMean && decltype(with_mean)::value;
+        if (n_mine > 0) {
+            gload(vblock);
             lstore(0);
-            __syncthreads();
-            while (s + G < nfull) {
+        }
+        __syncthreads();
+        size_t k = 0;
+        if (n_steady > 0) {
+            size_t s = vblock;
+            const WriteGate gate{a.gate_mask, a.gate_win};
+            int held = 0, parity = 0;          // pieces in the ring; which of the two flags this stage uses
+            size_t held_from = s;              // stage of the oldest piece
+            for (; k < n_steady; ++k, s += G) {
                 gload(s + G);              // in flight during the MFMAs below
                 compute(buf);
-                if (kMean && write_mean) mean_stage(buf, s);
+                if (kWrite) {
+                    hold_put(held, mean_piece(buf));
+                    ++held;
+                    // one thread looks at the clock; the whole workgroup acts on what it saw, after
+                    // the barrier below (flags alternate: the next look may come before a slow
+                    // wavefront has read this one)
+                    if (threadIdx.x == 0) gate_flag[parity] = gate.open() ? 1 : 0;
+                }
                 if (++since_flush == kGramFlush) {
                     since_flush = 0;
                     flush();
@@ -403,63 +484,37 @@ __global__ __launch_bounds__(kBlock *kHalves) __attribute__((amdgpu_waves_per_eu
                 lstore(buf ^ 1);           // the other buffer was last read before the previous barrier
                 __syncthreads();
                 buf ^= 1;
-                s += G;
+                if (kWrite) {
+                    const bool open = gate_flag[parity] != 0;
+                    parity ^= 1;
+                    // window open: out with everything held, then no loads until it closes;
+                    // ring full: cannot wait for a window
+                    if (open || held == kHoldStages) {
+                        hold_flush(held, held_from);
+                        held = 0;
+                        held_from = s + G;
+                        if (open) gate.wait_closed();
+                    }
+                }
             }
+            if (kWrite) hold_flush(held, held_from);
+        }
+        if (k < n_mine) {              // the last full stage
             compute(buf);
-            if (kMean && write_mean) mean_stage(buf, s);
+            if (kWrite) mean_store(mean_piece(buf), vblock + k * G);
         }
         // ragged tail (P not a multiple of the stage width): one workgroup, element-wise guarded loads
-        if (nfull * kStageElems < P && blockIdx.x == nfull % G) {
+        if (nfull * kStageElems < P && vblock == nfull % G) {
             __syncthreads();
             gload_guarded(nfull);
             lstore(0);
             __syncthreads();
             compute(0);
-            if (kMean && write_mean) mean_stage(0, nfull);
+            if (kWrite) mean_store_guarded(mean_piece(0), nfull);
         }
-    } else {
-        // Virtual workgroup v takes stages v, v + G, ... (the same stages, in the same order and
-        // with the same flush points as a workgroup of the branch above). The halves of a workgroup
-        // may differ by one stage while the barriers are common: both run the trip count of the
-        // first half, and a half without a stage left idles through the barriers.
-        const size_t first = size_t(blockIdx.x) * kHalves;
-        const size_t n_mine = nfull > vblock ? (nfull - vblock + G - 1) / G : 0;
-        const size_t n_trip = nfull > first ? (nfull - first + G - 1) / G : 0;
-        if (n_mine > 0) {
-            gload(vblock);
-            lstore(0);
-        }
-        __syncthreads();
-        for (size_t k = 0; k < n_trip; ++k) {
-            const size_t s = vblock + k * G;
-            const bool has = k < n_mine, has_next = k + 1 < n_mine;
-            if (has_next) gload(s + G);
-            if (has) {
-                compute(buf);
-                if (kMean && write_mean) mean_stage(buf, s);
-                if (has_next && ++since_flush == kGramFlush) {
-                    since_flush = 0;
-                    flush();
-                }
-            }
-            if (has_next) lstore(buf ^ 1);
-            __syncthreads();
-            buf ^= 1;
-        }
-        // ragged tail: one virtual workgroup (the condition of the barrier is uniform over the workgroup)
-        if (nfull * kStageElems < P && blockIdx.x == (nfull % G) / kHalves) {
-            const bool tail_mine = vblock == nfull % G;
-            if (tail_mine) {
-                gload_guarded(nfull);
-                lstore(0);
-            }
-            __syncthreads();
-            if (tail_mine) {
-                compute(0);
-                if (kMean && write_mean) mean_stage(0, nfull);
-            }
-        }
-    }
+    };
+    if (kMean && write_mean) run(std::true_type{});
+    else run(std::false_type{});
     flush();
 
     // Tile entry in accumulator register v of lane l: row i = 4*(l/16) + v, column j = l%16.

@@ -254,15 +254,6 @@ constexpr int fused_min_count(int groups)
     constexpr int f32_min[5] = {1, 4, 8, 8, 7};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
-// Halves per workgroup of the Gram kernel when it also writes the mean (see gram_kernel):
-// two where it was measured faster (bf16 rows in one or two groups: -7 % and -8 %), one where
-// it made no difference (binary32, one group) or cost 3-12 % (everything wider).
-template <typename T>
-constexpr int fused_gram_halves(int groups)
-{
-    return sizeof(T) == 2 && groups <= 2 ? 2 : 1;
-}
-
 // The same for a batch of N gradients. A guess carried over from the previous call is used on
 // shorter vectors, where the small-batch kernel gains from writing even a one-gradient "mean"
 // (the stand-alone pass would cost a launch and a second read of that gradient).
@@ -279,6 +270,29 @@ int spec_min_count(int N, bool carried)
 // With `mean_out` the launch also writes the mean of ctx->pred's accept set there (kFull only).
 // With `chunk_stride` the launch reads a sample instead: P / kSampleChunk runs of kSampleChunk
 // elements, run r starting at element r * chunk_stride of every gradient.
+// Write windows of a pass that reads `read_bytes` and writes `write_bytes` in all (see WriteGate):
+// period and window length in ticks of the 100 MHz clock. The window's share of the period is the
+// share of the pass's time that the writing needs (rates measured on MI355X: 7.0 TB/s reading,
+// 5.0 TB/s writing, 6.5 TB/s for the pass as a whole), plus a tenth. A workgroup looks at the clock
+// once per stage, so a window is at least 1.15 stages long; it can hold `hold_stages` stages'
+// results, so the period is about the time those take -- unless the window's minimum length asks
+// for a longer one (then results are also written when the ring is full: few bytes in that case).
+struct GateParams {
+    unsigned mask, win;
+};
+inline GateParams gate_params(double read_bytes, double write_bytes, double stage_bytes, int hold_stages)
+{
+    const double t_write = write_bytes / 5.0e12, t_total = read_bytes / 7.0e12 + t_write;
+    const double share = 1.1 * t_write / t_total;
+    const double stage_ticks = stage_bytes * kGramBlocks / 6.5e12 * 1e8;
+    const double win_min = 1.15 * stage_ticks;
+    unsigned lg = 10;
+    while (lg < 15 && double(2u << lg) <= hold_stages * stage_ticks) ++lg;      // largest period the ring covers
+    while (lg < 15 && share * double(1u << lg) < win_min) ++lg;                 // ... or what the window needs
+    const double win = share * double(1u << lg);
+    return {(1u << lg) - 1, (unsigned)(win < win_min ? win_min : win)};
+}
+
 template <typename T, int NG, int kMode>
 gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, const int (&groups)[4],
                        hipStream_t s, gaf_kernel_id id = GAF_K_GRAM, float *mean_out = nullptr,
@@ -307,11 +321,17 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
     if (chunk_stride)
         for (g.chunk_shift = 0; (size_t(1) << g.chunk_shift) < kStagesPerChunk;) ++g.chunk_shift;
     g.chunk_stride = chunk_stride;
+    if (mean_out) {
+        const double stage_bytes = 16.0 * NG * 256 * gram_stage_m(NG);
+        const GateParams gp = gate_params(double(N) * sizeof(T) * P, 4.0 * P, stage_bytes,
+                                          gram_hold_stages<T>(NG));
+        g.gate_mask = gp.mask;
+        g.gate_win = gp.win;
+    }
     {
         Timed t(ctx, s, id);
-        constexpr int kHalves = fused_gram_halves<T>(NG);
         if (mean_out && kMode == kFull)
-            gram_kernel<T, NG, kFull, true, kHalves><<<kGramBlocks / kHalves, kBlock * kHalves, 0, s>>>(g);
+            gram_kernel<T, NG, kFull, true><<<kGramBlocks, kBlock, 0, s>>>(g);
         else
             gram_kernel<T, NG, kMode><<<kGramBlocks, kBlock, 0, s>>>(g);
     }
