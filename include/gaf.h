@@ -66,7 +66,8 @@ typedef enum {
     GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace */
     GAF_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
     GAF_EUNSUPPORTED = 5, /* unknown dtype, or N outside the range of the requested form */
-    GAF_EDEVICE = 6       /* the context's device is not the calling thread's current device */
+    GAF_EDEVICE = 6,      /* the context's device is not the calling thread's current device */
+    GAF_ELIMIT = 7        /* N or P beyond the fixed limits of gaf_aggregate_static */
 } gaf_status;
 
 /* Element type of the micro-gradients. The aggregate and `out` are always binary32. */
@@ -310,6 +311,35 @@ gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N,
                                   gaf_dtype dt, float tau, int B, const size_t *bucket_offsets,
                                   float *out, uint8_t *accept_mask, float *cos_dist, int32_t *count,
                                   void *stream);
+
+/*
+ * gaf_aggregate for callers that cannot allocate device memory at all -- code
+ * running under HIP graph capture, serving loops that must not call hipMalloc,
+ * harnesses that forbid it -- and therefore cannot call gaf_create either.
+ * Same operation, arguments, results and schedule selection (AUTO) as
+ * gaf_aggregate; the workspace a context would own is a fixed array of about
+ * 10.6 MB in the global memory of every device the library's code is loaded on,
+ * held until the process ends. The call works on the calling thread's current
+ * device, enqueues on `stream` and calls no hipMalloc, hipFree or other
+ * allocating routine.
+ *   Limits: N <= GAF_STATIC_MAX_N and P <= GAF_STATIC_MAX_P, else GAF_ELIMIT
+ *   (nothing enqueued).
+ *   All calls on one device share that device's array, which keeps what the
+ *   last call left in it (including AUTO's record of guesses, as a context
+ *   would): calls that may overlap on one device -- different streams or
+ *   threads -- race on it. What has to start from zero is cleared by a small
+ *   kernel ahead of the first call's own kernels on each device.
+ * gaf_static_init looks up the current device's array ahead of time (one
+ * runtime query, no allocation, nothing enqueued); calling it is optional, but
+ * a caller that is about to start a graph capture should, so that the first
+ * gaf_aggregate_static inside the capture has nothing left to look up.
+ */
+#define GAF_STATIC_MAX_N 64
+#define GAF_STATIC_MAX_P ((size_t)1 << 36)
+gaf_status gaf_static_init(void);
+gaf_status gaf_aggregate_static(const void *const *grads, int N, size_t P, gaf_dtype dt, float tau,
+                                float *out, uint8_t *accept_mask, float *cos_dist, int32_t *count,
+                                void *stream);
 
 /*
  * Launch timing, for benchmarks (not part of the paper's method). Between

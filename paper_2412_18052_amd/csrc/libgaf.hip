@@ -4,6 +4,7 @@
 // synchronises and never reads a device result.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -734,6 +735,83 @@ gaf_status check_batch(const gaf_ctx *ctx, const void *const *grads, int N, size
     return GAF_OK;
 }
 
+// ---- the entry point that allocates nothing -----------------------------------------------
+// Its workspace is a fixed array in every device's global memory instead of a context's
+// allocations: the same blocks a context holds, laid out back to back. Host code never uses the
+// array's name as an address (in host code that name is only a handle for the runtime): the device
+// address is asked for once per device and kept.
+constexpr size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+constexpr size_t kStOffState = 0;
+constexpr size_t kStOffPartials = kStOffState + align256(sizeof(State));
+constexpr size_t kStOffGramWs = kStOffPartials + align256(sizeof(double) * 3 * kMaxBlocks);
+constexpr size_t kStOffGramFull = kStOffGramWs + align256(sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile);
+constexpr size_t kStOffAccepted = kStOffGramFull + align256(sizeof(double) * GAF_STATIC_MAX_N * GAF_STATIC_MAX_N);
+constexpr size_t kStOffSeedWs = kStOffAccepted + align256(sizeof(int32_t) * GAF_STATIC_MAX_N);
+constexpr size_t kStOffSegWs = kStOffSeedWs + align256(sizeof(SeedWs));
+constexpr size_t kStOffPred = kStOffSegWs + align256(sizeof(SegWs));
+constexpr size_t kStaticScratchBytes = kStOffPred + align256(sizeof(Prediction));
+static_assert(GAF_STATIC_MAX_N == kBatchMaxN, "the fixed workspace serves the Gram-first schedule's batch sizes");
+static_assert(kStaticScratchBytes <= (size_t(11) << 20), "the fixed workspace is meant to stay modest (about 10.6 MB)");
+
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 64;
+std::mutex g_static_mutex;
+gaf_ctx g_static_ctx[kStaticMaxDevices];      // pointers into each device's copy of `scratch`
+bool g_static_ready[kStaticMaxDevices];
+bool g_static_cleared[kStaticMaxDevices];     // the clearing kernel has been enqueued once
+
+// Zeroes the parts of the fixed workspace that a context gets zeroed at creation (decision state,
+// Gram matrix, record of guesses). A kernel rather than a memset, so that a caller may capture it.
+struct StaticClear {
+    unsigned char *base;
+    size_t off[3], bytes[3];
+};
+__global__ void static_clear_kernel(StaticClear c)
+{
+    for (int r = 0; r < 3; ++r)
+        for (size_t b = size_t(blockIdx.x) * blockDim.x + threadIdx.x; b < c.bytes[r] / 4;
+             b += size_t(gridDim.x) * blockDim.x)
+            reinterpret_cast<uint32_t *>(c.base + c.off[r])[b] = 0u;
+}
+
+// The current device's fixed-workspace context, set up on first use: the device address of this
+// device's copy of `scratch` is looked up (the only runtime query; no allocation) and the
+// context's pointers are set into it.
+gaf_status static_context(gaf_ctx **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return GAF_EHIP;
+    if (dev < 0 || dev >= kStaticMaxDevices) return GAF_ELIMIT;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    gaf_ctx *c = &g_static_ctx[dev];
+    if (!g_static_ready[dev]) {
+        unsigned char *base = nullptr;
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&base), HIP_SYMBOL(scratch)) != hipSuccess || !base) {
+            (void)hipGetLastError();
+            return GAF_EHIP;
+        }
+        c->device = dev;
+        c->max_P = GAF_STATIC_MAX_P;
+        c->max_N = GAF_STATIC_MAX_N;
+        c->st = reinterpret_cast<State *>(base + kStOffState);
+        c->partials = reinterpret_cast<double *>(base + kStOffPartials);
+        c->gram_ws = reinterpret_cast<double *>(base + kStOffGramWs);
+        c->gram_full = reinterpret_cast<double *>(base + kStOffGramFull);
+        c->accepted = reinterpret_cast<int32_t *>(base + kStOffAccepted);
+        c->seed_ws = reinterpret_cast<SeedWs *>(base + kStOffSeedWs);
+        c->seg_ws = reinterpret_cast<SegWs *>(base + kStOffSegWs);
+        c->pred = reinterpret_cast<Prediction *>(base + kStOffPred);
+        c->pred_reset = false;
+        c->schedule = GAF_SCHEDULE_AUTO;
+        c->prof_on = false;
+        c->prof_cap = 0;
+        g_static_ready[dev] = true;
+    }
+    *out = c;
+    return GAF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -748,6 +826,7 @@ const char *gaf_strerror(gaf_status status)
     case GAF_EHIP: return "HIP runtime call or kernel launch failed";
     case GAF_EUNSUPPORTED: return "unsupported element type, or batch size outside the range of the requested form";
     case GAF_EDEVICE: return "context's device is not the current device";
+    case GAF_ELIMIT: return "size beyond the fixed limits of the entry point that allocates nothing";
     }
     return "unknown status";
 }
@@ -1052,6 +1131,43 @@ gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P,
     hipStream_t s = static_cast<hipStream_t>(stream);
     return dt == GAF_F32 ? pairwise_impl<float>(ctx, grads, N, P, D, gram, s)
                          : pairwise_impl<bf16_t>(ctx, grads, N, P, D, gram, s);
+}
+
+gaf_status gaf_static_init(void)
+{
+    gaf_ctx *ctx = nullptr;
+    return static_context(&ctx);
+}
+
+gaf_status gaf_aggregate_static(const void *const *grads, int N, size_t P, gaf_dtype dt, float tau,
+                                float *out, uint8_t *accept_mask, float *cos_dist, int32_t *count,
+                                void *stream)
+{
+    if (!grads || N < 1 || P == 0 || !out || !accept_mask || !cos_dist || !count) return GAF_EINVAL;
+    if (N > GAF_STATIC_MAX_N || P > GAF_STATIC_MAX_P) return GAF_ELIMIT;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (misaligned(out)) return GAF_EALIGN;
+    for (int i = 0; i < N; ++i) {
+        if (!grads[i] || grads[i] == static_cast<const void *>(out)) return GAF_EINVAL;
+        if (misaligned(grads[i])) return GAF_EALIGN;
+    }
+    gaf_ctx *ctx = nullptr;
+    const gaf_status rc = static_context(&ctx);
+    if (rc != GAF_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        // first call on this device: the workspace starts from zero like a fresh context's
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (!g_static_cleared[ctx->device]) {
+            StaticClear c{reinterpret_cast<unsigned char *>(ctx->st),
+                          {kStOffState, kStOffGramFull, kStOffPred},
+                          {sizeof(State), sizeof(double) * GAF_STATIC_MAX_N * GAF_STATIC_MAX_N, sizeof(Prediction)}};
+            static_clear_kernel<<<8, kBlock, 0, s>>>(c);
+            if (launched() != GAF_OK) return GAF_EHIP;
+            g_static_cleared[ctx->device] = true;
+        }
+    }
+    return aggregate_dispatch(ctx, grads, N, P, dt, tau, out, accept_mask, cos_dist, count, s);
 }
 
 }  // extern "C"

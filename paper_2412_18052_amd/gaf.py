@@ -12,13 +12,14 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgaf.so")
 
-GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEVICE = range(7)
+GAF_OK, GAF_EINVAL, GAF_EALIGN, GAF_ENOMEM, GAF_EHIP, GAF_EUNSUPPORTED, GAF_EDEVICE, GAF_ELIMIT = range(8)
+GAF_STATIC_MAX_N, GAF_STATIC_MAX_P = 64, 1 << 36
 GAF_F32, GAF_BF16 = 0, 1
 
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
            "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram",
            "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed",
-           "gaf_aggregate_with_matrix", "gaf_fused_mean_record")
+           "gaf_aggregate_with_matrix", "gaf_fused_mean_record", "gaf_static_init", "gaf_aggregate_static")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -87,6 +88,11 @@ def load(path=None):
     lib.gaf_set_schedule.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_fused_mean_record.restype = c.c_int
     lib.gaf_fused_mean_record.argtypes = [c.c_void_p, c.POINTER(c.c_int32)]
+    lib.gaf_static_init.restype = c.c_int
+    lib.gaf_static_init.argtypes = []
+    lib.gaf_aggregate_static.restype = c.c_int
+    lib.gaf_aggregate_static.argtypes = [c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int, c.c_float,
+                                         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.gaf_profile_begin.restype = c.c_int
     lib.gaf_profile_begin.argtypes = [c.c_void_p, c.c_int]
     lib.gaf_profile_end.restype = c.c_int
@@ -198,6 +204,20 @@ def gaf_aggregate(ctx, grads, tau, out=None, accept_mask=None, cos_dist=None, co
     _check(load().gaf_aggregate(ctx.handle, table, N, P, code, float(tau), _ptr(out),
                                 _ptr(accept_mask), _ptr(cos_dist), _ptr(count),
                                 _stream_handle(stream)), "gaf_aggregate")
+    return out, accept_mask, cos_dist, count
+
+
+def gaf_static_init():
+    """Looks up the current device's fixed workspace ahead of the first gaf_aggregate_static."""
+    _check(load().gaf_static_init(), "gaf_static_init")
+
+
+def gaf_aggregate_static(grads, tau, out, accept_mask, cos_dist, count, stream=None):
+    """gaf_aggregate without a context and without any allocation: every output is the caller's."""
+    table, P, code = _grad_table(grads)
+    _check(load().gaf_aggregate_static(table, len(grads), P, code, float(tau), _ptr(out), _ptr(accept_mask),
+                                       _ptr(cos_dist), _ptr(count), _stream_handle(stream)),
+           "gaf_aggregate_static")
     return out, accept_mask, cos_dist, count
 
 
