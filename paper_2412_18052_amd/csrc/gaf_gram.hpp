@@ -213,7 +213,12 @@ constexpr int gram_hold_stages(int ng) { return gram_hold_stages_for(int(sizeof(
 template <typename T, int NG, int kMode, bool kMean = false, bool kSplit = (sizeof(T) == 4 && NG >= 3)>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) void gram_kernel(GramArgs a)
 {
-    const int tid = int(threadIdx.x);
+    // Lane from the execution mask and wavefront index as a scalar, so that nothing in the loops
+    // depends on the register the thread index arrives in (the compiler was seen to spill that
+    // register and to reload it inside the stage loop, behind a wait for every load in flight).
+    const int lane = int(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)));
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int tid = wave * 64 + lane;
     const size_t vblock = blockIdx.x;
     // a sampling launch has nothing to do while a backoff runs: no guess will be written
     if (a.chunk_stride != 0 && a.pred->backoff > 0) return;
@@ -245,7 +250,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     __shared__ const void *row_table[kGramRows];
     __shared__ int gate_flag[2];
 
-    const int lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, sub = lane >> 4;
 
     // pointer table into LDS, read with compile-time indices so that it stays in
@@ -258,20 +262,21 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         row_table[threadIdx.x] = p;
     }
     // kMean: LDS word offset, within a stage buffer, of the k-th gradient of the guessed accept set
-    // (visiting order); entries past the guess point at the zero row. Uniform, so they live in
-    // scalar registers and the LDS reads of mean_piece depend on nothing but the stage buffer.
+    // (visiting order); entries past the guess point at the zero row. The table lives in LDS; a
+    // stage's mean reads it back four entries at a time (the same address in every lane) and moves
+    // them to scalar registers, so that the row reads that follow are "scalar offset plus the
+    // thread's columns" and no register is tied up between stages.
+    __shared__ __attribute__((aligned(16))) int32_t pred_off[kGramRows];
     int c_pred = 0;
     bool write_mean = false;
-    int pred_word[kMean ? kRows : 1];
     if (kMean) {
         c_pred = a.pred->count;
         write_mean = a.carry_n ? carried_guess_writes(a.pred, a.carry_n, a.min_count) : a.pred->write != 0;
         if (!write_mean) c_pred = 0;
         if (c_pred > kRows) c_pred = kRows;
-#pragma unroll
-        for (int k = 0; k < kRows; ++k) {
-            const int r = k < c_pred ? a.pred->list[k] : -1;
-            pred_word[k] = __builtin_amdgcn_readfirstlane((r >= 0 && r < kRows ? r : kRows) * kRowWords);
+        if (tid < kRows) {
+            const int r = tid < c_pred ? a.pred->list[tid] : -1;
+            pred_off[tid] = (r >= 0 && r < kRows ? r : kRows) * kRowWords;
         }
         for (int w = tid; w < kRowWords; w += kBlock)
             stage[kRows * kRowWords + w] = stage[kStageWords + kRows * kRowWords + w] = 0u;
@@ -374,34 +379,36 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         }
     };
     // Eq. 5 over the guessed accept set for the stage in buffer `buf`: a thread adds, for each of
-    // its four columns, the guessed rows in visiting order. All 16 NG reads are issued at once
-    // (their addresses are scalar offsets plus the thread's columns); rows past the guess read the
-    // zero row, and adding +0 changes no bit of a sum that started from +0.
+    // its four columns, the guessed rows in visiting order, four rows' reads issued at once; rows
+    // past the guess read the zero row, and adding +0 changes no bit of a sum that started from +0.
     const float inv_c = 1.0f / (float)(c_pred > 0 ? c_pred : 1);
     auto mean_piece = [&](int buf) {
         f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
         if (tid < kQuads) {
             const uint32_t *src = &stage[buf * kStageWords + (sizeof(T) == 4 ? 4 : 2) * tid];
+            typedef int32_t i32x4_t __attribute__((ext_vector_type(4)));
+            for (int k0 = 0; k0 < c_pred; k0 += 4) {      // uniform trip count
+                const i32x4_t off = *reinterpret_cast<const i32x4_t *>(&pred_off[k0]);
+                int o[4];
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                if (16 * g >= c_pred) break;          // uniform
+                for (int k = 0; k < 4; ++k) o[k] = __builtin_amdgcn_readfirstlane(off[k]);
                 if (sizeof(T) == 4) {
-                    u32x4_t w[16];
+                    u32x4_t w[4];
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32x4_t *>(src + pred_word[16 * g + k]);
+                    for (int k = 0; k < 4; ++k) w[k] = *reinterpret_cast<const u32x4_t *>(src + o[k]);
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) {
+                    for (int k = 0; k < 4; ++k) {
                         sum.x += __uint_as_float(w[k].x);
                         sum.y += __uint_as_float(w[k].y);
                         sum.z += __uint_as_float(w[k].z);
                         sum.w += __uint_as_float(w[k].w);
                     }
                 } else {
-                    u32x2_t w[16];
+                    u32x2_t w[4];
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) w[k] = *reinterpret_cast<const u32x2_t *>(src + pred_word[16 * g + k]);
+                    for (int k = 0; k < 4; ++k) w[k] = *reinterpret_cast<const u32x2_t *>(src + o[k]);
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) {
+                    for (int k = 0; k < 4; ++k) {
                         sum.x += __uint_as_float(w[k].x << 16);
                         sum.y += __uint_as_float(w[k].x & 0xffff0000u);
                         sum.z += __uint_as_float(w[k].y << 16);
@@ -475,7 +482,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
                     // one thread looks at the clock; the whole workgroup acts on what it saw, after
                     // the barrier below (flags alternate: the next look may come before a slow
                     // wavefront has read this one)
-                    if (threadIdx.x == 0) gate_flag[parity] = gate.open() ? 1 : 0;
+                    if (wave == 0 && lane == 0) gate_flag[parity] = gate.open() ? 1 : 0;
                 }
                 if (++since_flush == kGramFlush) {
                     since_flush = 0;
