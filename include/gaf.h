@@ -206,6 +206,38 @@ gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i,
                     void *stream);
 
 /*
+ * Streaming form with one step of look-ahead: the same visit of Algorithm 1's
+ * inner loop as gaf_step -- same decision, same D_i, same count -- but the update
+ * of the aggregate for an accepted g_i is NOT applied by this call. It stays
+ * pending and is applied by the next gaf_step_lookahead on the same aggregate, in
+ * the very walk over the vectors that takes the sums for the next gradient (one
+ * pass over the aggregate per visit instead of two), or by gaf_flush.
+ *
+ *   After the call (and until the pending update has been applied) `accum` holds
+ *   the mean of the gradients accepted BEFORE g_i, while *count already includes
+ *   g_i; cos_dist_out and accepted_out are final.
+ *   g_i must stay valid and unmodified until the NEXT gaf_step_lookahead or
+ *   gaf_flush on this context has run on the device -- one call longer than with
+ *   gaf_step.
+ *   A context carries one pending gradient: consecutive calls must name the same
+ *   accum, count, P and dtype (GAF_EINVAL otherwise), on the same stream. Any
+ *   other call on the context that uses its decision state (gaf_step, the batch
+ *   entry points) first applies a pending update on its own stream.
+ *   Results are those of gaf_step, bit for bit, once the pending update is applied.
+ * Two kernels per visit: update + sums in one walk, then the decision.
+ */
+gaf_status gaf_step_lookahead(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                              gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
+                              void *stream);
+
+/*
+ * Applies the update gaf_step_lookahead left pending, if any (one kernel; no memory
+ * traffic if that gradient was rejected). Afterwards accum is the mean of all
+ * accepted gradients, as after gaf_step.
+ */
+gaf_status gaf_flush(gaf_ctx *ctx, void *stream);
+
+/*
  * Diagnostic: Eq. 4 between every pair of the N micro-gradients, the quantity
  * the paper logs over training (Sec. 1, Fig. 1c/d).
  *

@@ -35,13 +35,26 @@ constexpr int kBatchMaxN = 64;   // gradients the Gram-first schedule handles (o
 // Gram matrix. Lane k carries the k-th accepted index; the dot product is a
 // fixed-tree wavefront sum. Outputs are indexed by gradient index.
 // Runs on ONE full wavefront (all 64 lanes active). Returns c.
+// *closest (optional) receives the smallest |D - tau| over the visited gradients: how close the
+// run came to deciding otherwise.
+// |running sum|^2 is carried as nn_g + 2 dot + nn_i. When the accepted gradients nearly cancel
+// (an anti-aligned gradient admitted with tau near 2) that expression can round to a value that
+// is tiny next to its terms, or negative. Below the resolution of the inner products -- 2^-40 of
+// the sum of the accepted |g_j|^2 for the binary64 sums of small batches (N <= 8), 2^-18 for the
+// matrix-core sums, whose tiles spend up to eight stages in binary32 -- it is rounding noise, and
+// the running sum is treated as the zero vector (distance 1 by definition) rather than letting
+// sqrt(< 0) or a random cosine decide about everything that follows.
 __device__ __forceinline__ int run_filter(const double *gram, int N, int seed, float tau,
-                                          uint8_t *mask, float *cos_dist, int32_t *accepted_list)
+                                          uint8_t *mask, float *cos_dist, int32_t *accepted_list,
+                                          double *closest = nullptr)
 {
     const int lane = threadIdx.x & 63;
     int my_index = lane == 0 ? seed : -1;   // lane k < c holds the k-th accepted gradient
     int c = 1;
     double nn_g = gram[size_t(seed) * N + seed];   // |running sum|^2
+    double nn_terms = nn_g;                        // sum of the accepted |g_j|^2
+    const double cancel_eps = N <= 8 ? 0x1p-40 : 0x1p-18;
+    double near = 4.0;
     if (lane == 0) {
         mask[seed] = 1;
         cos_dist[seed] = 0.f;
@@ -54,6 +67,9 @@ __device__ __forceinline__ int run_filter(const double *gram, int N, int seed, f
         const double nn_i = gram[size_t(i) * N + i];
         const double D = distance_from_sums(dot, nn_g, nn_i);
         const bool accept = D <= (double)tau;      // false for NaN
+        const double gap = fabs(D - (double)tau);
+        if (gap != gap) near = 0.0;                // a NaN distance counts as "as close as it gets"
+        else if (gap < near) near = gap;
         if (lane == 0) {
             mask[i] = accept ? 1 : 0;
             cos_dist[i] = (float)D;
@@ -62,11 +78,19 @@ __device__ __forceinline__ int run_filter(const double *gram, int N, int seed, f
             if (lane == c) my_index = i;
             if (lane == 0) accepted_list[c] = i;
             nn_g = nn_g + 2.0 * dot + nn_i;
+            nn_terms += nn_i;
+            if (nn_g <= cancel_eps * nn_terms) nn_g = 0.0;
             ++c;
         }
     }
+    if (closest) *closest = near;
     return c;
 }
+
+// A guess made from a sample is acted on only if every sampled distance kept this far from tau
+// (four standard errors of a cosine estimated from 2^22 elements): in training the distances crowd
+// around tau (Fig. 1), and a guess that is a coin toss costs a wasted write of the whole result.
+constexpr double kSpecMargin = 2e-3;
 
 // What a filter launch does with the context's Prediction.
 enum : int { kSpecNone = 0, kSpecGuess = 1, kSpecVerify = 2, kSpecVerifyCarried = 3 };
@@ -97,7 +121,8 @@ __device__ __forceinline__ void filter_body(const double *gram, int N, float tau
         }
         return;
     }
-    const int c = run_filter(gram, N, 0, tau, mask, cos_dist, accepted_list);
+    double closest = 0.0;
+    const int c = run_filter(gram, N, 0, tau, mask, cos_dist, accepted_list, &closest);
     if (threadIdx.x == 0) {
         count[0] = c;
         st->count = c;
@@ -106,7 +131,9 @@ __device__ __forceinline__ void filter_body(const double *gram, int N, float tau
     }
     if (spec == kSpecGuess) {
         if (threadIdx.x == 0) {
-            pred->write = (c >= min_count && pred->backoff == 0) ? 1 : 0;
+            // a guess is written only if no decision of the sampled run was a close call: a
+            // cosine estimated from the sample is off by about 1 / sqrt(sample size) = 5e-4
+            pred->write = (c >= min_count && pred->backoff == 0 && closest >= kSpecMargin) ? 1 : 0;
             pred->valid = 0;
             pred->n = N;
         }
@@ -208,7 +235,7 @@ __global__ __launch_bounds__(64) void seed_select_kernel(const SeedWs *ws, int N
 constexpr int kMeanClaim = 4;            // tiles a workgroup of the mean kernel claims per counter access
 constexpr int kMeanQueueBlocks = 2048;   // workgroups of a mean launch that claims its tiles
 constexpr size_t kMeanQueueMinTiles = 32768;   // ... used from this many tiles up (one workgroup per tile below)
-constexpr int kSmallMaxN = 8;
+constexpr int kSmallMaxN = 8;            // (run_filter's resolution rule assumes this 8)
 constexpr int kSmallMaxPairs = kSmallMaxN * (kSmallMaxN + 1) / 2;
 constexpr int kSmallBlocks = 512;       // workgroups of the small-batch Gram kernel (<= kMaxBlocks)
 

@@ -154,6 +154,7 @@ __global__ __launch_bounds__(kBlock) void decide_kernel(PassArgs a, int nb)
             st->seed = 1;
             if (a.cos_out) a.cos_out[0] = 0.f;
             if (a.mask_out) a.mask_out[0] = 1;
+            if (a.count_out) a.count_out[0] = 1;
         }
         return;
     }
@@ -212,6 +213,30 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(PassArgs a)
     const bool apply = (a.pend != nullptr) && (a.st->accept != 0);
     double dot = 0.0, nn_g = 0.0, nn_i = 0.0;
     if (apply)
+        walk<T, kUpdate, true, kStream>(a, 1.0f / (float)c_prev, dot, nn_g, nn_i);
+    else
+        walk<T, kKeep, true, kStream>(a, 0.f, dot, nn_g, nn_i);
+    publish_partials(a, dot, nn_g, nn_i);
+}
+
+// Streaming with one step of look-ahead: the visit of g_i first applies what the previous visit
+// decided about ITS gradient (a.pend; the decision is in the device state: rejected, accepted, or
+// accepted as the seed) and takes the sums for g_i on the aggregate as it then stands -- one walk
+// instead of an updating walk plus a reducing one. The decision about g_i itself is left pending
+// in turn. a.count_in is the caller's counter: c including the pending gradient; zero there
+// means g_i is the seed and there is nothing to compare it with.
+template <typename T, bool kStream>
+__global__ __launch_bounds__(kBlock) void step_reduce_kernel(PassArgs a)
+{
+    const int32_t c_prev = *a.count_in;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.st->c_prev = c_prev;
+    if (c_prev == 0) return;
+    const bool apply = (a.pend != nullptr) && (a.st->accept != 0);
+    const bool seed = apply && (a.st->seed != 0);
+    double dot = 0.0, nn_g = 0.0, nn_i = 0.0;
+    if (seed)
+        walk<T, kAdopt, true, kStream>(a, 0.f, dot, nn_g, nn_i);
+    else if (apply)
         walk<T, kUpdate, true, kStream>(a, 1.0f / (float)c_prev, dot, nn_g, nn_i);
     else
         walk<T, kKeep, true, kStream>(a, 0.f, dot, nn_g, nn_i);

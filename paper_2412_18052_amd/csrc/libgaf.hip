@@ -29,6 +29,12 @@ struct gaf_ctx {
     Prediction *pred;    // device, accept set predicted from a sample (fused mean) and the record of earlier guesses
     bool pred_reset;     // that record is to be cleared by the next call that guesses
     gaf_schedule schedule;
+    // streaming with look-ahead: the gradient whose decision (in `st`) has not been applied yet
+    const void *pend_g;
+    float *pend_accum;
+    int32_t *pend_count;
+    size_t pend_P;
+    gaf_dtype pend_dt;
     // launch timing (off unless gaf_profile_begin was called)
     bool prof_on;
     int prof_cap;
@@ -237,6 +243,70 @@ gaf_status step_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i
         } else {
             decide_update_kernel<T, kStream><<<grid, block, 0, s>>>(a, grid.x);
         }
+    }
+    return launched();
+}
+
+// Applies the update a look-ahead visit left pending (no memory traffic if that gradient was
+// rejected) and forgets it.
+template <typename T, bool kStream>
+gaf_status flush_impl(gaf_ctx *ctx, hipStream_t s)
+{
+    PassArgs a{};
+    a.P = ctx->pend_P;
+    a.st = ctx->st;
+    a.partials = ctx->partials;
+    a.acc = ctx->pend_accum;
+    a.dst = ctx->pend_accum;
+    a.pend = ctx->pend_g;
+    {
+        Timed t(ctx, s, GAF_K_UPDATE);
+        update_kernel<T, kStream><<<tile_blocks(a.P), kBlock, 0, s>>>(a);
+    }
+    return launched();
+}
+
+gaf_status flush_pending(gaf_ctx *ctx, hipStream_t s)
+{
+    if (!ctx->pend_g) return GAF_OK;
+    const size_t P = ctx->pend_P;
+    const gaf_status rc =
+        ctx->pend_dt == GAF_F32
+            ? (stream_loads(P, 4) ? flush_impl<float, true>(ctx, s) : flush_impl<float, false>(ctx, s))
+            : (stream_loads(P, 2) ? flush_impl<bf16_t, true>(ctx, s) : flush_impl<bf16_t, false>(ctx, s));
+    ctx->pend_g = nullptr;
+    return rc;
+}
+
+// One visit with look-ahead: two launches (update of the pending gradient + sums for g_i in one
+// walk; decision). The update for g_i stays pending.
+template <typename T, bool kStream>
+gaf_status step_lookahead_impl(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                               float tau, float *cos_out, uint8_t *acc_out, hipStream_t s)
+{
+    // the launch shape of gaf_step's reducing pass: same partial sums, same distances, bit for bit
+    const dim3 grid(pass_blocks(P, P >= kStepSplitMinP ? kMaxBlocks : kStepBlocks)), block(kBlock);
+    PassArgs a{};
+    a.P = P;
+    a.st = ctx->st;
+    a.partials = ctx->partials;
+    a.tau = tau;
+    a.acc = accum;
+    a.dst = accum;
+    a.pend = ctx->pend_g;
+    a.next = g_i;
+    a.count_in = count;
+    {
+        Timed t(ctx, s, GAF_K_REDUCE);
+        step_reduce_kernel<T, kStream><<<grid, block, 0, s>>>(a);
+    }
+    if (launched() != GAF_OK) return GAF_EHIP;
+    a.cos_out = cos_out;
+    a.mask_out = acc_out;
+    a.count_out = count;
+    {
+        Timed t(ctx, s, GAF_K_DECIDE);
+        decide_kernel<<<1, block, 0, s>>>(a, grid.x);     // reads *count: 0 means g_i seeds
     }
     return launched();
 }
@@ -463,6 +533,11 @@ constexpr size_t kSpecMinP = size_t(1) << 26;
 // (no sample: it would cost too large a share); below it the calls are launch-bound and a
 // writing Gram pass gains nothing.
 constexpr size_t kCarryMinP = size_t(1) << 21;
+// ... and only for batches of two, the setting of the paper's own experiments, where the guess is
+// "the second gradient was accepted last time (or was not)": measured on batches of 8 gradients of
+// 11.2 M elements drawn independently, the exact accept set of the previous call was never this
+// call's (0 of 20), so larger batches do not guess on short vectors.
+constexpr int kCarryN = 2;
 
 // Distance in elements between the starts of consecutive runs of the sample for vectors of
 // length P >= kSpecMinP: the runs spread over the whole vector, the last one ends inside it.
@@ -492,7 +567,7 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     // and the guess is checked afterwards. Long vectors: guessed from a sample. Shorter ones:
     // the previous call's accept set.
     const bool speculate = !gram && !opt.best_seed && !opt.theta && ctx->schedule == GAF_SCHEDULE_AUTO &&
-                           P >= kCarryMinP;
+                           (P >= kSpecMinP || (P >= kCarryMinP && N == kCarryN));
     const bool carried = speculate && P < kSpecMinP;
     const bool small = N <= kSmallMaxN;
     if (speculate && ctx->pred_reset) {
@@ -621,6 +696,7 @@ gaf_status gram_first_dispatch(gaf_ctx *ctx, const void *const *grads, int N, si
                                float tau, const BatchOptions &gram, float *out, uint8_t *mask,
                                float *cos_dist, int32_t *count, hipStream_t s)
 {
+    if (flush_pending(ctx, s) != GAF_OK) return GAF_EHIP;
     // the masked mean reads up to N gradients of s bytes and writes 4 bytes per element
     const bool st = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
     if (dt == GAF_F32)
@@ -705,6 +781,7 @@ gaf_status aggregate_dispatch(gaf_ctx *ctx, const void *const *grads, int N, siz
                               int32_t *count, hipStream_t s)
 {
     if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
+    if (flush_pending(ctx, s) != GAF_OK) return GAF_EHIP;
     const bool gram_first = ctx->schedule == GAF_SCHEDULE_GRAM ||
                             (ctx->schedule == GAF_SCHEDULE_AUTO && N >= 2 && N <= kBatchMaxN);
     if (gram_first)
@@ -803,6 +880,7 @@ gaf_status static_context(gaf_ctx **out)
         c->seg_ws = reinterpret_cast<SegWs *>(base + kStOffSegWs);
         c->pred = reinterpret_cast<Prediction *>(base + kStOffPred);
         c->pred_reset = false;
+        c->pend_g = nullptr;
         c->schedule = GAF_SCHEDULE_AUTO;
         c->prof_on = false;
         c->prof_cap = 0;
@@ -854,6 +932,7 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->prof_cap = 0;
     ctx->schedule = GAF_SCHEDULE_AUTO;
     ctx->pred_reset = false;
+    ctx->pend_g = nullptr;
     const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
     bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->st), sizeof(State)) == hipSuccess &&
@@ -1045,6 +1124,7 @@ gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N,
     }
     if (ctx->schedule == GAF_SCHEDULE_GRAM && (N < 2 || N > kBatchMaxN)) return GAF_EUNSUPPORTED;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (flush_pending(ctx, st) != GAF_OK) return GAF_EHIP;
     if (N <= kSmallMaxN && B <= kSegMaxBuckets && ctx->schedule != GAF_SCHEDULE_SEQUENTIAL) {
         const bool big = (size_t(N) * (dt == GAF_F32 ? 4 : 2) + 4) * P > (size_t(256) << 20);
         if (dt == GAF_F32)
@@ -1107,6 +1187,7 @@ gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i,
     if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
     if (misaligned(accum) || misaligned(g_i)) return GAF_EALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (flush_pending(ctx, s) != GAF_OK) return GAF_EHIP;
     if (dt == GAF_F32)
         return stream_loads(P, 4)
                    ? step_impl<float, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
@@ -1114,6 +1195,49 @@ gaf_status gaf_step(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i,
     return stream_loads(P, 2)
                ? step_impl<bf16_t, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
                : step_impl<bf16_t, false>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+}
+
+gaf_status gaf_step_lookahead(gaf_ctx *ctx, float *accum, int32_t *count, const void *g_i, size_t P,
+                              gaf_dtype dt, float tau, float *cos_dist_out, uint8_t *accepted_out,
+                              void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    if (!accum || !count || !g_i || P == 0 || g_i == static_cast<const void *>(accum))
+        return GAF_EINVAL;
+    if (P > ctx->max_P) return GAF_EINVAL;
+    if (dt != GAF_F32 && dt != GAF_BF16) return GAF_EUNSUPPORTED;
+    if (misaligned(accum) || misaligned(g_i)) return GAF_EALIGN;
+    // a pending gradient belongs to one running aggregate: the same (accum, count, P, dtype)
+    if (ctx->pend_g && (ctx->pend_accum != accum || ctx->pend_count != count || ctx->pend_P != P ||
+                        ctx->pend_dt != dt || ctx->pend_g == g_i))
+        return GAF_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == GAF_F32)
+        rc = stream_loads(P, 4)
+                 ? step_lookahead_impl<float, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
+                 : step_lookahead_impl<float, false>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+    else
+        rc = stream_loads(P, 2)
+                 ? step_lookahead_impl<bf16_t, true>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s)
+                 : step_lookahead_impl<bf16_t, false>(ctx, accum, count, g_i, P, tau, cos_dist_out, accepted_out, s);
+    if (rc != GAF_OK) {
+        ctx->pend_g = nullptr;
+        return rc;
+    }
+    ctx->pend_g = g_i;
+    ctx->pend_accum = accum;
+    ctx->pend_count = count;
+    ctx->pend_P = P;
+    ctx->pend_dt = dt;
+    return GAF_OK;
+}
+
+gaf_status gaf_flush(gaf_ctx *ctx, void *stream)
+{
+    gaf_status rc = check_ctx(ctx);
+    if (rc != GAF_OK) return rc;
+    return flush_pending(ctx, static_cast<hipStream_t>(stream));
 }
 
 gaf_status gaf_pairwise(gaf_ctx *ctx, const void *const *grads, int N, size_t P, gaf_dtype dt,

@@ -19,7 +19,8 @@ GAF_F32, GAF_BF16 = 0, 1
 SYMBOLS = ("gaf_create", "gaf_destroy", "gaf_strerror", "gaf_aggregate", "gaf_step", "gaf_pairwise",
            "gaf_profile_begin", "gaf_profile_end", "gaf_set_schedule", "gaf_aggregate_with_gram",
            "gaf_aggregate_best_seed", "gaf_aggregate_sgd", "gaf_aggregate_bucketed",
-           "gaf_aggregate_with_matrix", "gaf_fused_mean_record", "gaf_static_init", "gaf_aggregate_static")
+           "gaf_aggregate_with_matrix", "gaf_fused_mean_record", "gaf_static_init", "gaf_aggregate_static",
+           "gaf_step_lookahead", "gaf_flush")
 GAF_SCHEDULE_AUTO, GAF_SCHEDULE_SEQUENTIAL, GAF_SCHEDULE_GRAM = 0, 1, 2
 SCHEDULES = {"auto": 0, "sequential": 1, "gram": 2}
 KERNEL_NAMES = ("init", "seed_reduce", "reduce", "update", "gram", "gram_finalize", "distance", "decide",
@@ -63,6 +64,10 @@ def load(path=None):
     lib.gaf_step.restype = c.c_int
     lib.gaf_step.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_int,
                              c.c_float, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gaf_step_lookahead.restype = c.c_int
+    lib.gaf_step_lookahead.argtypes = lib.gaf_step.argtypes
+    lib.gaf_flush.restype = c.c_int
+    lib.gaf_flush.argtypes = [c.c_void_p, c.c_void_p]
     lib.gaf_pairwise.restype = c.c_int
     lib.gaf_pairwise.argtypes = [c.c_void_p, c.POINTER(c.c_void_p), c.c_int, c.c_size_t, c.c_int,
                                  c.c_void_p, c.c_void_p, c.c_void_p]
@@ -317,6 +322,25 @@ def gaf_step(ctx, accum, count, g_i, tau, cos_dist_out=None, accepted_out=None, 
     _check(load().gaf_step(ctx.handle, _ptr(accum), _ptr(count), _ptr(g_i), g_i.numel(),
                            _dtype_code(g_i), float(tau), _ptr(cos_dist_out), _ptr(accepted_out),
                            _stream_handle(stream)), "gaf_step")
+
+
+def gaf_step_lookahead(ctx, accum, count, g_i, tau, cos_dist_out=None, accepted_out=None, stream=None):
+    """One streaming visit whose update of accum stays pending until the next such call or
+    gaf_flush; g_i must stay alive until then."""
+    if not g_i.is_cuda or not g_i.is_contiguous() or g_i.dim() != 1:
+        raise ValueError("g_i must be a contiguous 1-D device tensor")
+    if accum.dtype != torch.float32 or accum.numel() != g_i.numel() or not accum.is_contiguous():
+        raise ValueError("accum must be contiguous float32 of the gradient's length")
+    if count.dtype != torch.int32 or count.numel() != 1:
+        raise ValueError("count must be a single int32 on the device")
+    _check(load().gaf_step_lookahead(ctx.handle, _ptr(accum), _ptr(count), _ptr(g_i), g_i.numel(),
+                                     _dtype_code(g_i), float(tau), _ptr(cos_dist_out), _ptr(accepted_out),
+                                     _stream_handle(stream)), "gaf_step_lookahead")
+
+
+def gaf_flush(ctx, stream=None):
+    """Applies the update gaf_step_lookahead left pending, if any."""
+    _check(load().gaf_flush(ctx.handle, _stream_handle(stream)), "gaf_flush")
 
 
 def gaf_pairwise(ctx, grads, D=None, gram=None, stream=None):

@@ -552,10 +552,11 @@ def test_fused_mean_backs_off_after_wrong_guesses(ctx):
 @pytest.mark.parametrize("N,P,dtype", [(2, (1 << 21) + 7, "f32"), (2, 11_220_132, "bf16"), (5, (1 << 21) + 4097, "f32"),
                                        (12, (1 << 21) + 3, "f32"), (20, 1 << 21, "bf16"), (40, (1 << 21) + 33, "f32")])
 def test_carried_guess_on_shorter_vectors(ctx, oracle, N, P, dtype):
-    """Below the length where a sample pays, the guess is the previous call's accept set (same N).
-    Three batches: X and a second draw X2 with the same agreement pattern (guess right), Y with
-    another pattern (guess wrong). Every result is checked against the oracle, must equal the
-    two-pass schedule's bit for bit, and the record must follow the hits and misses."""
+    """Below the length where a sample pays, batches of TWO gradients guess the previous call's
+    accept set; larger batches do not guess at these lengths. Three batches: X and a second draw X2
+    with the same agreement pattern (guess right), Y with another pattern (guess wrong). Every
+    result is checked against the oracle, must equal the two-pass schedule's bit for bit, and the
+    record must follow the hits and misses (N = 2) or show that nothing was written (N > 2)."""
     if ctx.schedule_name != "auto":
         pytest.skip("the fused mean belongs to the AUTO schedule")
     gen = torch.Generator().manual_seed(1000 + N)
@@ -575,6 +576,14 @@ def test_carried_guess_on_shorter_vectors(ctx, oracle, N, P, dtype):
         expect[k] = [t.clone() for t in gaf.gaf_aggregate(ctx, dev[k], 0.9)]
     assert ref["X"][1].tolist() == ref["X2"][1].tolist() != ref["Y"][1].tolist()
     gaf.gaf_set_schedule(ctx, "auto")
+    if N != 2:
+        for step, k in enumerate(("X", "X2", "X", "Y", "Y", "X")):
+            res = gaf.gaf_aggregate(ctx, dev[k], 0.9)
+            assert gaf.gaf_fused_mean_record(ctx)["write"] == 0, (step, k)
+            check_against_oracle(res, ref[k], dtype)
+            for x, y in zip(res, expect[k]):
+                assert torch.equal(x, y), (step, k)
+        return
     # (batch, was a mean written by the Gram pass, was it right, backoff after, penalty after)
     script = [("X", 0, 0, 0, 1),       # nothing to carry yet
               ("X2", 1, 1, 0, 1), ("X", 1, 1, 0, 1),
@@ -588,9 +597,60 @@ def test_carried_guess_on_shorter_vectors(ctx, oracle, N, P, dtype):
         check_against_oracle(res, ref[k], dtype)
         for x, y in zip(res, expect[k]):
             assert torch.equal(x, y), (step, k)
-    # another batch size does not inherit the guess
-    res = gaf.gaf_aggregate(ctx, dev["X"][: N - 1] if N > 2 else dev["X"] + dev["X"][:1], 0.9)
-    assert gaf.gaf_fused_mean_record(ctx)["write"] == 0
+    # another batch size does not use the guess (three gradients do not guess at this length at all)
+    res = [t.clone() for t in gaf.gaf_aggregate(ctx, dev["X"] + dev["Y"][1:], 0.9)]
+    gaf.gaf_set_schedule(ctx, "gram")
+    for x, y in zip(res, gaf.gaf_aggregate(ctx, dev["X"] + dev["Y"][1:], 0.9)):
+        assert torch.equal(x, y)
+    gaf.gaf_set_schedule(ctx, "auto")
+
+
+@pytest.mark.parametrize("N", [3, 9, 33])
+def test_near_cancellation_at_tau_two(ctx, oracle, N):
+    """g_2 = -g_1 up to noise of 1e-3: the running sum after g_2 nearly cancels. With tau = 2
+    everything is accepted and the result is the plain mean (Eq. 2) on every schedule -- the
+    running sum's squared norm, carried through the Gram matrix as a difference of large terms,
+    must not turn into a negative or random number there."""
+    P = 300_000
+    gen = torch.Generator().manual_seed(77 + N)
+    g1 = torch.randn(P, generator=gen)
+    grads = [g1, -g1 + 1e-3 * torch.randn(P, generator=gen)]
+    grads += [torch.randn(P, generator=gen) for _ in range(N - 2)]
+    res = gaf.gaf_aggregate(ctx, [g.cuda() for g in grads], 2.0)
+    ref = oracle.aggregate(oracle_arrays(grads), np.float32(2.0))
+    torch.cuda.synchronize()
+    assert ref[1].tolist() == [1] * N
+    assert res[1].cpu().numpy().tolist() == [1] * N and int(res[3].item()) == N
+    mean = oracle.plain_average(oracle_arrays(grads))
+    assert rel_l2(res[0].cpu().numpy(), mean) <= 1e-5
+    d = np.abs(res[2].cpu().numpy().astype(np.float64) - ref[2])
+    # The distance of g_3 is taken against a running sum of relative size 1e-3: binary64 sums
+    # (sequential passes, small batches) resolve it; the matrix-core sums do not (their entries
+    # carry binary32 rounding of the same size) and report the distance to a zero vector, 1.
+    if ctx.schedule_name == "sequential" or N <= 8:
+        assert d.max() <= 1e-4, d
+    else:
+        assert d[2] <= 1e-2 and np.delete(d, 2).max() <= 1e-4, d      # |cos| of unrelated vectors: a few / sqrt(P)
+
+
+@pytest.mark.parametrize("N,P", [(9, 3000), (33, 2500), (64, 4100), (17, 40_000)])
+def test_highly_correlated_rows_on_short_vectors(ctx, oracle, N, P):
+    """|cos| near 0.99 between all rows and few columns per workgroup: the matrix-core tiles sum
+    in binary32 for up to eight stages before they are added into binary64 totals, and with so few
+    columns nothing averages that rounding out -- the distances must still be within 1e-6."""
+    gen = torch.Generator().manual_seed(5 * N + P)
+    base = torch.randn(P, generator=gen)
+    grads = [base + 0.14 * torch.randn(P, generator=gen) for _ in range(N)]
+    a = oracle_arrays(grads)
+    oD, _ = oracle.pairwise(a)
+    assert 0.005 < oD[0, 1] < 0.03
+    D = gaf.gaf_pairwise(ctx, [g.cuda() for g in grads])
+    torch.cuda.synchronize()
+    assert np.max(np.abs(D.cpu().numpy().astype(np.float64) - oD)) <= DIST_ATOL
+    for tau in (0.015, 0.5):
+        ref = oracle.aggregate(a, np.float32(tau))
+        if np.all(np.abs(ref[2][1:] - np.float32(tau)) >= MARGIN):
+            check_against_oracle(gaf.gaf_aggregate(ctx, [g.cuda() for g in grads], tau), ref, "f32")
 
 
 @pytest.mark.timeout(600)
