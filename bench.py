@@ -1,23 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the GAF filter-and-average hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--configs all|none|a,b,..]
 
-One "step" is one pass of the whole hot path over one batch of synthetic
-micro-gradients already resident in HBM: a full gaf_aggregate (batch
-workloads), N gaf_step calls (streaming), or gaf_aggregate_with_matrix
-(diagnostic: distance matrix plus filter). Prints ONE JSON line.
+One "step" is one pass of the whole hot path over one batch of synthetic micro-gradients that are
+already resident in HBM: a full gaf_aggregate (batch workloads), N streaming visits
+(gaf_step_lookahead, then gaf_flush) for `streaming`, or gaf_aggregate_with_matrix (`diagnostic`:
+distance matrix plus filter). Prints ONE JSON line: the headline workload (default `large`) at the top
+level and, under "configs", one entry each for the other listed workloads, for the streaming entry
+point on the `large` batch, and for `large` with thresholds placed next to a distance.
 
-Vectors of 2^21 .. 2^26 elements: the batch call guesses each call's accept set from the previous
-call's. Timing one batch over and over would make every guess right, which no training run
-does; so for those sizes the steps cycle through several independently drawn batches
-(--batches, default 4), and the run with one repeated batch is reported separately under
-other_schedules as the all-guesses-right bound.
-
-value = effective HBM GB/s = (bytes the method itself must move) / time:
-    per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted (write it),
-    once per batch        s*P + 4*P for the seed,
-    pairwise              N*s*P (every gradient read once).
+Two byte counts per step, both stated:
+  schedule bytes  what the executed schedule must move: the algorithmic bytes of every launch
+                  (table in the design doc). value = schedule bytes / time -- a real bandwidth, never
+                  above the HBM peak.
+  B_min           what the method as the paper states it (one visit per gradient) must move:
+                  per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted,
+                  once per batch        s*P + 4*P for the seed,  pairwise  N*s*P.
+                  bmin_equivalent_gbps = B_min / time says how fast a sequential implementation
+                  would have to stream to take the same time; the Gram-first schedule moves fewer
+                  bytes than B_min, so this figure can exceed the HBM peak and is NOT a bandwidth.
 """
 import argparse
 import hashlib
@@ -30,10 +32,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
-PEAK_MFMA_F32_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E, published
+PEAK_MFMA_F32_TFLOPS = 157.3    # MI355X dense fp32 matrix, published
 PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
-PEAK_VALU_F64_TFLOPS = 78.6   # MI355X fp64 vector, published
+PEAK_VALU_F64_TFLOPS = 78.6     # MI355X fp64 vector, published
+SPEC_SAMPLE = 1 << 22           # elements of every gradient a sampling launch reads
+SPEC_MIN_P = 1 << 26            # vectors from this length on guess the accept set from a sample
+CARRY_MIN_P = 1 << 21           # batches of two from this length on carry the guess from call to call
+WORKLOADS = ["tiny", "resnet18", "streaming", "large", "diagnostic"]
+EXTRA_CONFIGS = ["large_step", "large_near_tau"]
 
 
 def source_digest():
@@ -51,13 +58,12 @@ def source_digest():
     return h.hexdigest()[:16]
 
 
-def bmin_bytes(w, mask):
-    s, P = w.elem_bytes, w.P
+def bmin_bytes(s, P, mask, pairwise=False):
     total = s * P + 4 * P
-    for i in range(1, w.N):
-        total += s * P + 4 * P + (4 * P if mask[i] else 0)
-    if w.mode == "pairwise":
-        total += w.N * s * P
+    for a in mask[1:]:
+        total += s * P + 4 * P + (4 * P if a else 0)
+    if pairwise:
+        total += len(mask) * s * P
     return total
 
 
@@ -66,111 +72,287 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large",
-                    choices=["tiny", "resnet18", "streaming", "large", "diagnostic"])
+    ap.add_argument("--workload", default="large", choices=WORKLOADS, help="the headline workload")
     ap.add_argument("--schedule", default="auto", choices=["auto", "sequential", "gram"],
                     help="schedule of the batch call (auto = Gram-first for N <= 64)")
+    ap.add_argument("--configs", default="all",
+                    help="'all', 'none' or a comma-separated list out of %s: the entries of the "
+                         "\"configs\" array beside the headline" % ",".join(WORKLOADS + EXTRA_CONFIGS))
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (launch-bound sizes)")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--P", type=int, default=None, help="override the vector length")
-    ap.add_argument("--N", type=int, default=None, help="override the number of micro-gradients")
-    ap.add_argument("--batches", type=int, default=0,
-                    help="independently drawn batches (seeds seed, seed+1, ...) the steps cycle through; "
-                         "0 = 4 where the library carries guesses from call to call, else 1")
+    ap.add_argument("--P", type=int, default=None, help="override the headline's vector length")
+    ap.add_argument("--N", type=int, default=None, help="override the headline's number of micro-gradients")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="ELEMS",
                     help="before anything else run one plain copy of ELEMS binary32 elements through "
                          "the library (a single-gradient batch: reads 4*ELEMS bytes, writes 4*ELEMS): "
                          "the known-size dispatch that profiler byte counters are scaled by")
     ap.add_argument("--only-profile-loop", action="store_true",
-                    help="for runs under a profiler: skip the timed loop, the other schedules, the ceilings "
-                         "and the CPU baseline, so that the last --steps launches of every kernel are exactly "
-                         "the ones the per-kernel figures (roofline) are computed from")
+                    help="for runs under a profiler: the headline's per-kernel loop only (no timed loop, no "
+                         "other schedules, configs, ceilings or CPU baseline), so that the last --steps "
+                         "launches of every kernel are exactly the ones the roofline is computed from")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle baseline sample (0 disables it)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the library runs on one GPU only (no collectives, no sharding); "
                  "use --gpus 1")
+    if args.configs == "all":
+        args.configs = [c for c in WORKLOADS + EXTRA_CONFIGS if c != args.workload]
+    elif args.configs == "none" or args.only_profile_loop:
+        args.configs = []
+    else:
+        args.configs = [c for c in args.configs.split(",") if c]
+        for c in args.configs:
+            if c not in WORKLOADS + EXTRA_CONFIGS:
+                sys.exit("bench.py: unknown config %r" % c)
+    if args.only_profile_loop:
+        args.configs = []
     return args
-
 
 
 def hbm_roof(alg_bytes, avg_ms):
     ach = alg_bytes / (avg_ms * 1e-3) / 1e9
-    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-            "frac": ach / PEAK_HBM_GBPS}
+    return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBPS}
 
 
-def kernel_rooflines(w, steps, B, per_kernel, records, masks, counts):
-    """Roofline of each streaming kernel from its launch durations in the per-kernel loop:
-    {kernel: (roofline dict, mean launch ms, algorithmic bytes per launch, total ms)}.
-    records: the library's record of guesses after each step of that loop ([] where nothing is
-    guessed); masks, counts: accept mask and count of each of the B batches."""
-    P, N, s = w.P, w.N, w.elem_bytes
-    roofs = {}
-    if "gram" in per_kernel:
-        # one launch reads every gradient once
-        dur = per_kernel["gram"]
-        avg_ms = sum(dur) / len(dur)
-        alg_bytes = float(N * s * P)
-        if records:                 # launches that also wrote the mean of their guess
-            assert len(dur) == len(records)
-            alg_bytes += 4.0 * P * sum(r["write"] for r in records) / len(records)
-        r = hbm_roof(alg_bytes, avg_ms)
-        if N <= 8:
-            # vector-ALU kernel: one binary64 FMA per pair (i <= j) per element
-            flops = 2.0 * (N * (N + 1) // 2) * P
-            frac2 = flops / (avg_ms * 1e-3) / 1e12 / PEAK_VALU_F64_TFLOPS
-            if frac2 > r["frac"]:
-                r = {"bound": "alu", "achieved": flops / (avg_ms * 1e-3) / 1e12,
-                     "peak": PEAK_VALU_F64_TFLOPS, "unit": "TFLOP/s", "frac": frac2, "hbm_frac": r["frac"]}
-            else:
-                r["alu_frac"] = frac2
+class Run:
+    """One workload under one schedule: buffers, the step, timing and the per-kernel figures."""
+
+    def __init__(self, gaf, torch, w, batches, mode, schedule, taus=None):
+        self.gaf, self.torch, self.w, self.batches, self.mode = gaf, torch, w, batches, mode
+        self.schedule = schedule
+        P, N = w.P, w.N
+        self.taus = taus or [w.tau] * len(batches)
+        self.ctx = gaf.gaf_create(max_P=P, max_N=max(N, 64))
+        gaf.gaf_set_schedule(self.ctx, schedule)
+        dev = "cuda"
+        self.out = torch.empty(P, dtype=torch.float32, device=dev)
+        self.mask = torch.empty(N, dtype=torch.uint8, device=dev)
+        self.dist = torch.empty(N, dtype=torch.float32, device=dev)
+        self.count = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.D = torch.empty((N, N), dtype=torch.float32, device=dev) if mode == "matrix" else None
+        self.G = torch.empty((N, N), dtype=torch.float64, device=dev) if mode == "matrix" else None
+        gram_first = schedule != "sequential" and 2 <= N <= 64 and mode in ("aggregate", "matrix")
+        self.sampled = gram_first and schedule == "auto" and P >= SPEC_MIN_P
+        self.carried = gram_first and schedule == "auto" and CARRY_MIN_P <= P < SPEC_MIN_P and N == 2
+        if mode in ("step", "step_plain"):
+            self.schedule_used = "streaming_lookahead" if mode == "step" else "streaming"
+        elif not gram_first:
+            self.schedule_used = "sequential"
         else:
-            # matrix-core kernel: 16-row groups, one 16x16 tile per pair of groups. binary32 rows in
-            # three or four groups are multiplied through a three-way bfloat16 split (six bf16 MFMAs
-            # per product), everything else in its own type.
+            self.schedule_used = "gram_first_fused_mean" if self.sampled else "gram_first"
+        self.masks, self.dists, self.counts = [], [], []
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.gaf.gaf_destroy(self.ctx)
+
+    def step(self, k=0):
+        gaf, b = self.gaf, k % len(self.batches)
+        grads, tau = self.batches[b], self.taus[b]
+        if self.mode == "step":
+            self.count.zero_()
+            for i, g in enumerate(grads):
+                gaf.gaf_step_lookahead(self.ctx, self.out, self.count, g, tau, self.dist[i:i + 1], self.mask[i:i + 1])
+            gaf.gaf_flush(self.ctx)
+        elif self.mode == "step_plain":
+            self.count.zero_()
+            for i, g in enumerate(grads):
+                gaf.gaf_step(self.ctx, self.out, self.count, g, tau, self.dist[i:i + 1], self.mask[i:i + 1])
+        elif self.mode == "matrix" and self.schedule != "sequential":
+            # the distance matrix and the filter share one Gram pass
+            gaf.gaf_aggregate_with_matrix(self.ctx, grads, tau, self.out, self.mask, self.dist, self.count, self.D, self.G)
+        else:
+            if self.mode == "matrix":
+                gaf.gaf_pairwise(self.ctx, grads, D=self.D)
+            gaf.gaf_aggregate(self.ctx, grads, tau, self.out, self.mask, self.dist, self.count)
+
+    def prepare(self, warmup):
+        """Every batch once (its accept mask, for the byte counts), then the warm-up."""
+        torch = self.torch
+        for b in range(len(self.batches)):
+            self.step(b)
+            torch.cuda.synchronize()
+            self.masks.append(self.mask.cpu().numpy().tolist())
+            self.dists.append(self.dist.cpu().numpy().tolist())
+            self.counts.append(int(self.count.item()))
+        for k in range(warmup):
+            self.step(k)
+        torch.cuda.synchronize()
+
+    def timed(self, steps, graph=False):
+        torch = self.torch
+        run_step = self.step
+        if graph:
+            # the library neither allocates nor synchronises in its calls, so a step can be captured
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                self.step()
+            torch.cuda.current_stream().wait_stream(side)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self.step()
+            run_step = lambda k=0: g.replay()
+            run_step()
+            torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for k in range(steps):
+            run_step(k)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms = 1e3 * (time.perf_counter() - t0) / steps
+        return wall_ms, ev0.elapsed_time(ev1) / steps
+
+    def profile(self, steps):
+        """Per-kernel durations over `steps` steps, HIP events on the launch stream; where the Gram
+        pass may write the mean of a guess, the library's record says after each step whether it
+        did and whether the guess was right (reading it waits for the device: not in the timed loop)."""
+        gaf = self.gaf
+        gaf.gaf_profile_begin(self.ctx, 65536)
+        records = []
+        for k in range(steps):
+            self.step(k)
+            if self.sampled or self.carried:
+                records.append(gaf.gaf_fused_mean_record(self.ctx))
+        times = gaf.gaf_profile_end(self.ctx, 65536)
+        per_kernel = {}
+        for name, ms in times:
+            per_kernel.setdefault(name, []).append(ms)
+        return per_kernel, records, len(times) // steps
+
+    # ---- algorithmic bytes of every launch of the per-kernel loop, by kernel ----
+    def launch_bytes(self, steps, per_kernel, records):
+        """{kernel: [bytes of each launch, None for launches that return at once]} in launch order."""
+        w, B = self.w, len(self.batches)
+        P, N, s = w.P, w.N, w.elem_bytes
+        out = {}
+        if self.mode in ("step", "step_plain"):
+            red, upd = [], []
+            for k in range(steps):
+                m = self.masks[k % B]
+                for i in range(N):
+                    if self.mode == "step_plain":
+                        red.append(None if i == 0 else (4 + s) * P)
+                        upd.append(((s + 4) * P if i == 0 else (8 + s) * P) if m[i] else None)
+                    elif i == 0:
+                        red.append(None)                       # the seed: nothing to compare with
+                    elif i == 1:
+                        red.append(2 * s * P + 4 * P)          # adopt the seed, sums for g_2
+                    else:
+                        red.append((4 + s) * P + ((s + 4) * P if m[i - 1] else 0))
+                if self.mode == "step":
+                    upd.append(((s + 4) * P if N == 1 else (8 + s) * P) if m[N - 1] else None)   # the flush
+            out["reduce"], out["update"] = red, upd
+            return out
+        if "gram" in per_kernel:
+            # pairwise in front of a sequential aggregate launches the Gram kernel too
+            n = len(per_kernel["gram"])
+            wrote = [r["write"] for r in records] if records else [0] * n
+            out["gram"] = [N * s * P + (4 * P if wrote[k % len(wrote)] else 0) for k in range(n)]
+        if "gram_sample" in per_kernel:
+            out["gram_sample"] = [N * s * SPEC_SAMPLE] * len(per_kernel["gram_sample"])
+        if "mean" in per_kernel:
+            out["mean"] = [None if (records and records[k]["valid"]) else self.counts[k % B] * s * P + 4 * P
+                           for k in range(len(per_kernel["mean"]))]
+        if "seed_reduce" in per_kernel:
+            out["seed_reduce"] = [2 * s * P + 4 * P] * len(per_kernel["seed_reduce"])
+        if "reduce" in per_kernel:
+            out["reduce"] = [(4 + s) * P + ((s + 4) * P if self.masks[k % B][i - 1] else 0)
+                             for k in range(steps) for i in range(2, N)]
+        if "update" in per_kernel:
+            if N == 1:
+                out["update"] = [(s + 4) * P] * len(per_kernel["update"])
+            else:
+                out["update"] = [(8 + s) * P if self.masks[k % B][N - 1] else None for k in range(steps)]
+        return out
+
+    def kernel_table(self, steps, per_kernel, records):
+        """Per kernel: launches that do work, mean duration, algorithmic bytes per launch, roofline."""
+        lb = self.launch_bytes(steps, per_kernel, records)
+        w = self.w
+        N, P = w.N, w.P
+        table = {}
+        for name, dur in per_kernel.items():
+            entry = {"launches_per_step": len(dur) / steps, "avg_launch_ms": sum(dur) / len(dur),
+                     "total_ms_per_step": sum(dur) / steps}
+            if name in lb:
+                assert len(lb[name]) == len(dur), (name, len(lb[name]), len(dur))
+                live = [(b, d) for b, d in zip(lb[name], dur) if b is not None]
+                if live:
+                    alg = sum(b for b, _ in live) / len(live)
+                    avg = sum(d for _, d in live) / len(live)
+                    r = hbm_roof(alg, avg)
+                    entry.update({"avg_launch_ms": avg, "algorithmic_bytes_per_launch": alg,
+                                  "launches_with_work_per_step": len(live) / steps, "roofline": r,
+                                  "bytes_per_step": sum(b for b, _ in live) / steps})
+                    if name == "gram":
+                        self._compute_bound(r, avg)
+            table[name] = entry
+        return table
+
+    def _compute_bound(self, r, avg_ms):
+        """The Gram kernel's arithmetic side: if its fraction of the matrix (or binary64 vector)
+        peak exceeds the memory fraction, that names the bound."""
+        w = self.w
+        N, P = w.N, w.P
+        if N <= 8:
+            flops, peak, key = 2.0 * (N * (N + 1) // 2) * P, PEAK_VALU_F64_TFLOPS, "alu"
+        else:
             ng = (N + 15) // 16
             flops = 2.0 * (ng * (ng + 1) // 2) * 256 * P
-            peak_tf = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
-            if w.dtype == "f32" and ng >= 3:
-                flops *= 6
-                peak_tf = PEAK_MFMA_BF16_TFLOPS
-            mfma_frac = flops / (avg_ms * 1e-3) / 1e12 / peak_tf
-            if mfma_frac > r["frac"]:
-                r = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": peak_tf,
-                     "unit": "TFLOP/s", "frac": mfma_frac, "hbm_frac": r["frac"]}
-            else:
-                r["mfma_frac"] = mfma_frac
-        roofs["gram"] = (r, avg_ms, alg_bytes, sum(dur))
-    if "mean" in per_kernel:
-        # accepted gradients read once, result written once; a launch that finds the result in
-        # place (right guess) returns at once and is left out
-        dur = per_kernel["mean"]
-        assert len(dur) == steps
-        live = [k for k in range(steps) if not (records and records[k]["valid"])]
-        if live:
-            avg_ms = sum(dur[k] for k in live) / len(live)
-            alg_bytes = sum(float(counts[k % B] * s * P + 4 * P) for k in live) / len(live)
-            roofs["mean"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur[k] for k in live))
-    if "reduce" in per_kernel:
-        # launch k of a batch's reducing passes visits gradient i = k + 2 and stores the update of
-        # gradient i - 1 if that one was accepted; a streaming reduce never stores.
-        if w.mode == "step":
-            # the launch for the seed returns at once (nothing to compare with): not counted
-            per_launch = ([None] + [(4 + s) * P] * (N - 1)) * steps
+            peak = PEAK_MFMA_F32_TFLOPS if w.dtype == "f32" else PEAK_MFMA_BF16_TFLOPS
+            if w.dtype == "f32" and ng >= 3:       # three-way bfloat16 split: six bf16 MFMAs per product
+                flops, peak = 6 * flops, PEAK_MFMA_BF16_TFLOPS
+            key = "mfma"
+        frac = flops / (avg_ms * 1e-3) / 1e12 / peak
+        if frac > r["frac"]:
+            r.update({"bound": key, "hbm_frac": r["frac"], "achieved": flops / (avg_ms * 1e-3) / 1e12,
+                      "peak": peak, "unit": "TFLOP/s", "frac": frac})
         else:
-            per_launch = [(4 + s) * P + (4 * P if masks[k % B][i - 1] else 0)
-                          for k in range(steps) for i in range(2, N)]
-        dur = per_kernel["reduce"]
-        assert len(dur) == len(per_launch), (len(dur), len(per_launch))
-        dur = [d for k, d in enumerate(dur) if per_launch[k] is not None]
-        alg = sum(b for b in per_launch if b is not None)
-        avg_ms = sum(dur) / max(1, len(dur))
-        alg_bytes = alg / max(1, len(dur))
-        roofs["reduce"] = (hbm_roof(alg_bytes, avg_ms), avg_ms, alg_bytes, sum(dur))
-    return roofs
+            r[key + "_frac"] = frac
+
+
+def summarise(run, steps, wall_ms, events_ms, per_kernel, records, launches_per_step, traffic_db):
+    """The figures reported for one workload."""
+    w = run.w
+    P, N, s, B = w.P, w.N, w.elem_bytes, len(run.batches)
+    table = run.kernel_table(steps, per_kernel, records)
+    sched_bytes = sum(e.get("bytes_per_step", 0.0) for e in table.values())
+    bmin = sum(bmin_bytes(s, P, run.masks[k % B], run.mode == "matrix") for k in range(steps)) / steps
+    timed = [k for k in table if "roofline" in table[k]]
+    dom = max(timed, key=lambda k: table[k]["total_ms_per_step"])
+    roof = dict(table[dom]["roofline"])
+    roof.update({"kernel": dom, "avg_launch_ms": table[dom]["avg_launch_ms"],
+                 "algorithmic_bytes_per_launch": table[dom]["algorithmic_bytes_per_launch"], "traffic": None})
+    ent = traffic_db.get("%s/%s/%s" % (w.name, run.schedule_used, dom))
+    if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
+        # measured HBM bytes per launch of this kernel in the profiler run, as a ratio to the
+        # algorithmic bytes per launch of that same run; scaled to this run's launches
+        roof["traffic"] = ent["hbm_bytes_over_algorithmic"] * roof["algorithmic_bytes_per_launch"]
+        roof["traffic_over_algorithmic"] = ent["hbm_bytes_over_algorithmic"]
+    roof["other_kernels"] = {k: {"frac": table[k]["roofline"]["frac"], "bound": table[k]["roofline"]["bound"],
+                                 "avg_launch_ms": table[k]["avg_launch_ms"],
+                                 "algorithmic_bytes_per_launch": table[k]["algorithmic_bytes_per_launch"]}
+                             for k in timed if k != dom}
+    res = {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "mode": run.mode, "schedule": run.schedule_used,
+           "batches": B, "accepted_per_batch": run.counts, "launches_per_step": launches_per_step,
+           "schedule_bytes_per_step": sched_bytes, "bmin_bytes_per_step": bmin,
+           "kernel_ms": {k: v["avg_launch_ms"] for k, v in table.items()}, "roofline": roof,
+           "ms_per_step": wall_ms, "ms_per_step_hip_events": events_ms}
+    if wall_ms is not None:
+        t = wall_ms * 1e-3
+        res.update({"achieved_gbps": sched_bytes / t / 1e9, "achieved_frac_of_hbm_peak": sched_bytes / t / 1e9 / PEAK_HBM_GBPS,
+                    "bmin_equivalent_gbps": bmin / t / 1e9, "micro_gradients_per_s": N / t})
+    if records:
+        res["guesses"] = {"source": "sample of this call's gradients" if run.sampled else "previous call's accept set",
+                          "mean_written_by_gram_pass": sum(r["write"] for r in records),
+                          "right": sum(r["valid"] for r in records), "steps": len(records)}
+    return res
 
 
 def measure_ceilings(gaf, torch):
@@ -201,7 +383,7 @@ def measure_ceilings(gaf, torch):
         return {"error": repr(e)}
 
 
-def cpu_baseline(w, grads, seed, cpu_seconds, wl, np):
+def cpu_baseline(w, grads, mode, seed, cpu_seconds, wl, np):
     """The oracle, as it stands, on a bounded sample of the same workload: all N micro-gradients,
     the first Ps coordinates of each, Ps sized for about cpu_seconds of work."""
     from oracle import gaf_oracle
@@ -215,13 +397,13 @@ def cpu_baseline(w, grads, seed, cpu_seconds, wl, np):
     tp = time.perf_counter() - tp
     rate_guess = max(rate_guess, N * probe / max(tp, 1e-4))
     Ps = int(min(P, max(probe, cpu_seconds * rate_guess / N)))
-    if w.mode == "pairwise":
+    if mode == "matrix":
         Ps = int(min(P, max(1 << 16, Ps // 24)))   # the pair loop costs ~N/2 more passes
     host = [wl.to_host_array(g[:Ps]) for g in grads]
     tc = time.perf_counter()
-    if w.mode == "pairwise":
+    if mode == "matrix":
         gaf_oracle.pairwise(host)
-    if w.mode == "step":
+    if mode in ("step", "step_plain"):
         acc64 = np.empty(Ps, dtype=np.float64)
         cnt, o_mask = 0, []
         for h in host:
@@ -230,13 +412,104 @@ def cpu_baseline(w, grads, seed, cpu_seconds, wl, np):
     else:
         _, o_mask, _, _ = gaf_oracle.aggregate(host, np.float32(w.tau))
     tc = time.perf_counter() - tc
-    ws = wl.spec(w.name, seed, P=Ps, N=N)
-    cpu_bytes = bmin_bytes(ws, list(o_mask))
+    cpu_bytes = bmin_bytes(w.elem_bytes, Ps, list(o_mask), mode == "matrix")
     return {"value": cpu_bytes / tc / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
             "seconds": tc, "micro_gradients_per_s": N / tc * (Ps / P),
-            "sample": "all %d micro-gradients, first %d of %d coordinates each "
-                      "(%.3g of the workload); micro_gradients_per_s is scaled to full length"
+            "sample": "all %d micro-gradients, first %d of %d coordinates each (%.3g of the workload); value = "
+                      "B_min of the sample / time (the oracle runs the sequential algorithm, so B_min is what "
+                      "it moves at least); micro_gradients_per_s is scaled to full length"
                       % (N, Ps, P, Ps / P)}
+
+
+def mode_of(w):
+    return {"aggregate": "aggregate", "step": "step", "pairwise": "matrix"}[w.mode]
+
+
+def other_schedules(gaf, torch, w, batches, mode, steps, main_ms):
+    """The other schedules of the batch call on the first batch, repeated (fewer steps)."""
+    out = []
+    runs = []
+    if 2 <= w.N <= 64:
+        runs.append(("gram_two_pass", "gram"))
+    runs.append(("sequential", "sequential"))
+    k = steps if main_ms < 1.0 else max(3, steps // 4)
+    for label, sched in runs:
+        r = Run(gaf, torch, w, batches[:1], mode, sched)
+        r.prepare(1)
+        wall, _ = r.timed(k)
+        pk, rec, _ = r.profile(k)
+        tab = r.kernel_table(k, pk, rec)
+        entry = {"schedule": label, "steps": k, "ms_per_step": wall,
+                 "achieved_gbps": sum(e.get("bytes_per_step", 0.0) for e in tab.values()) / (wall * 1e-3) / 1e9,
+                 "kernel_ms": {n: v["avg_launch_ms"] for n, v in tab.items()},
+                 "kernel_hbm_frac": {n: v["roofline"].get("hbm_frac", v["roofline"]["frac"])
+                                     for n, v in tab.items() if "roofline" in v}}
+        out.append(entry)
+        r.close()
+    return out
+
+
+def run_config(name, gaf, torch, wl, np, args, traffic_db, shared):
+    """One entry of the "configs" array."""
+    steps = max(3, args.steps // 2)
+    if name == "large_step":
+        # the streaming entry point on the headline-sized batch: 16 visits of 1e9 bf16 elements
+        w, grads = shared.get("large") or wl.generate("large", args.seed, device="cuda")
+        shared["large"] = (w, grads)
+        r = Run(gaf, torch, w, [grads], "step", "auto")
+        steps = 3
+    elif name == "large_near_tau":
+        # `large`, but every batch is given a threshold 2.5e-4 beside one of its own distances (the
+        # regime of Fig. 1: distances crowd around tau): a guess from a sample (error about 5e-4) is
+        # then a coin toss. Three independently drawn batches in turn; AUTO against the two-pass schedule.
+        w, g0 = shared.get("large") or wl.generate("large", args.seed, device="cuda")
+        shared["large"] = (w, g0)
+        batches = [g0] + [wl.generate("large", args.seed + j, device="cuda")[1] for j in (1, 2)]
+        probe = Run(gaf, torch, w, batches, "aggregate", "gram")
+        probe.prepare(0)
+        taus = []
+        for b, d in enumerate(probe.dists):
+            j = min(range(1, w.N), key=lambda i: abs(d[i] - w.tau))
+            taus.append(float(np.float32(d[j] + (2.5e-4 if b % 2 == 0 else -2.5e-4))))
+        probe.close()
+        steps = 30
+        r = Run(gaf, torch, w, batches, "aggregate", "auto", taus)
+        r.prepare(2)
+        wall, ev = r.timed(steps)
+        pk, rec, lps = r.profile(steps)
+        res = summarise(r, steps, wall, ev, pk, rec, lps, traffic_db)
+        r.close()
+        r2 = Run(gaf, torch, w, batches, "aggregate", "gram", taus)
+        r2.prepare(2)
+        wall2, _ = r2.timed(steps)
+        r2.close()
+        res.update({"workload": "large_near_tau", "taus": taus, "two_pass_ms_per_step": wall2, "steps": steps,
+                    "note": "thresholds 2.5e-4 beside a distance of each batch; AUTO writes a guess only when no "
+                            "sampled distance came within 2e-3 of tau, so here it runs the two-pass schedule plus "
+                            "the sampling launches"})
+        del batches
+        return res
+    else:
+        w, grads = wl.generate(name, args.seed, device="cuda")
+        if name == "large":
+            shared["large"] = (w, grads)
+        r = Run(gaf, torch, w, [grads], mode_of(w), args.schedule)
+        if w.P <= (1 << 24):
+            steps = max(steps, 20)
+    r.prepare(2)
+    wall, ev = r.timed(steps)
+    pk, rec, lps = r.profile(steps)
+    res = summarise(r, steps, wall, ev, pk, rec, lps, traffic_db)
+    res["steps"] = steps
+    if name == "large_step":
+        res["workload"] = "large_step"
+    if name == "streaming" or name == "large_step":
+        p = Run(gaf, torch, w, r.batches, "step_plain", "auto")
+        p.prepare(1)
+        res["gaf_step_without_lookahead_ms_per_step"] = p.timed(steps)[0]
+        p.close()
+    r.close()
+    return res
 
 
 def main():
@@ -260,225 +533,97 @@ def main():
         gaf.gaf_destroy(cal_ctx)
         del src
 
+    traffic_db = {}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic_db = json.load(fh)
+
     t0 = time.time()
     w, grads = wl.generate(args.workload, args.seed, P=args.P, N=args.N, device="cuda")
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     P, N, s = w.P, w.N, w.elem_bytes
-    ctx = gaf.gaf_create(max_P=P, max_N=max(N, 64))
-    gaf.gaf_set_schedule(ctx, args.schedule)
-    if w.mode == "step":
-        schedule_used = "streaming"
-    elif args.schedule == "sequential" or not (2 <= N <= 64):
-        schedule_used = "sequential"
-    else:
-        schedule_used = "gram_first"
-    # long vectors on the matrix-core path: the Gram pass also writes the mean of a guessed accept set
-    fused = schedule_used == "gram_first" and args.schedule == "auto" and P >= (1 << 26)
-    if fused:
-        schedule_used = "gram_first_fused_mean"
-    # shorter vectors: the guess is the previous call's accept set
-    carried = schedule_used == "gram_first" and args.schedule == "auto" and (1 << 21) <= P < (1 << 26)
-    B = args.batches if args.batches > 0 else (4 if carried and not args.graph else 1)
-    batches = [grads] + [wl.generate(args.workload, args.seed + j, P=args.P, N=args.N, device="cuda")[1]
-                         for j in range(1, B)]
-    torch.cuda.synchronize()
-
-    out = torch.empty(P, dtype=torch.float32, device="cuda")
-    mask = torch.empty(N, dtype=torch.uint8, device="cuda")
-    dist = torch.empty(N, dtype=torch.float32, device="cuda")
-    count = torch.zeros(1, dtype=torch.int32, device="cuda")
-    D = torch.empty((N, N), dtype=torch.float32, device="cuda") if w.mode == "pairwise" else None
-    G = torch.empty((N, N), dtype=torch.float64, device="cuda") if w.mode == "pairwise" else None
-
-    state = {"schedule": args.schedule}
-
-    def step(k=0):
-        grads = batches[k % B]
-        if w.mode == "step":
-            count.zero_()
-            for i, g in enumerate(grads):
-                gaf.gaf_step(ctx, out, count, g, w.tau, dist[i:i + 1], mask[i:i + 1])
-        else:
-            if w.mode == "pairwise" and state["schedule"] != "sequential":
-                # the distance matrix and the filter share one Gram pass
-                gaf.gaf_aggregate_with_matrix(ctx, grads, w.tau, out, mask, dist, count, D, G)
-                return
-            if w.mode == "pairwise":
-                gaf.gaf_pairwise(ctx, grads, D=D)
-            gaf.gaf_aggregate(ctx, grads, w.tau, out, mask, dist, count)
-
-    # every batch once: its accept mask (for the bytes the method must move) and a warm-up
-    masks, dists, counts = [], [], []
-    for b in range(B):
-        step(b)
-        torch.cuda.synchronize()
-        masks.append(mask.cpu().numpy().tolist())
-        dists.append(dist.cpu().numpy().tolist())
-        counts.append(int(count.item()))
-    for k in range(args.warmup):
-        step(k)
-    torch.cuda.synchronize()
-    run_step = step
-    if args.graph:
-        # the library neither allocates nor synchronises in its calls, so a step can be captured
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        run_step = lambda k=0: graph.replay()
-        run_step()
-        torch.cuda.synchronize()
-    mask_h, dist_h, c_h = masks[0], dists[0], counts[0]
-    step_bytes = sum(bmin_bytes(w, masks[k % B]) for k in range(args.steps)) / args.steps
-    ms_per_step = ms_per_step_events = value = None
+    mode = mode_of(w)
+    head = Run(gaf, torch, w, [grads], mode, args.schedule)
+    head.prepare(args.warmup)
+    wall = ev = None
     if not args.only_profile_loop:
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        ev0.record()
-        for k in range(args.steps):
-            run_step(k)
-        ev1.record()
-        torch.cuda.synchronize()
-        wall_s = time.perf_counter() - t0
-        ms_per_step = 1e3 * wall_s / args.steps
-        ms_per_step_events = ev0.elapsed_time(ev1) / args.steps
-        value = step_bytes / (ms_per_step * 1e-3) / 1e9
+        wall, ev = head.timed(args.steps, args.graph)
+    pk, rec, lps = head.profile(args.steps)
+    res = summarise(head, args.steps, wall, ev, pk, rec, lps, traffic_db)
+    roof = res["roofline"]
 
-    # ---- per-kernel durations over the same steps, HIP events on the launch stream; where the
-    # Gram pass may write the mean of a guess, the library's record says after each step whether
-    # it did and whether the guess was right (reading it waits for the device: not in the timed loop)
-    gaf.gaf_profile_begin(ctx, 65536)
-    records = []
-    for k in range(args.steps):
-        step(k)
-        if fused or carried:
-            records.append(gaf.gaf_fused_mean_record(ctx))
-    times = gaf.gaf_profile_end(ctx, 65536)
-    per_kernel = {}
-    for name, ms in times:
-        per_kernel.setdefault(name, []).append(ms)
-    launches_per_step = len(times) // args.steps
-
-    roofs = kernel_rooflines(w, args.steps, B, per_kernel, records, masks, counts)
-    dom = max(roofs, key=lambda k: roofs[k][3])      # the kernel the step spends most time in
-    roof, avg_ms, alg_bytes, _ = roofs[dom]
-    roof["kernel"] = dom
-    roof["avg_launch_ms"] = avg_ms
-    roof["algorithmic_bytes_per_launch"] = alg_bytes
-    roof["traffic"] = None
-    roof["other_kernels"] = {k: {"frac": v[0]["frac"], "bound": v[0]["bound"], "avg_launch_ms": v[1],
-                                 "algorithmic_bytes_per_launch": v[2]}
-                             for k, v in roofs.items() if k != dom}
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as fh:
-            tj = json.load(fh)
-        # measured HBM bytes per launch of this kernel in the profiler run, as a ratio to the
-        # algorithmic bytes per launch of that same run; scaled to this run's launches
-        ent = tj.get("%s/%s/%s" % (w.name, schedule_used, dom))
-        if ent and ent.get("source_digest") == source_digest() and ent.get("P") == P:
-            roof["traffic"] = ent["hbm_bytes_over_algorithmic"] * alg_bytes
-            roof["traffic_over_algorithmic"] = ent["hbm_bytes_over_algorithmic"]
-
-    # ---- the other schedules of the batch call, for comparison (fewer steps) ----
-    other = None
-    if w.mode != "step" and args.schedule == "auto" and 2 <= N <= 64 and not args.only_profile_loop:
-        other = []
-        # (label, schedule); all on the first batch, repeated
-        runs = [("gram_two_pass", "gram")] if fused or carried else []
-        if carried and not args.graph:
-            runs.append(("gram_first_one_batch_repeated_every_guess_right", "auto"))
-        runs.append(("sequential", "sequential"))
-        for label, sched in runs:
-            gaf.gaf_set_schedule(ctx, sched)
-            state["schedule"] = sched
-            # short steps: as many as the main loop, or the host's launch overhead shows
-            k = args.steps if ms_per_step < 1.0 else max(3, args.steps // 4)
-            step()
-            step()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(k):
-                step()
-            torch.cuda.synchronize()
-            ms_o = 1e3 * (time.perf_counter() - t0) / k
-            gaf.gaf_profile_begin(ctx, 65536)      # per-kernel times in a loop of their own: the event
-            for _ in range(k):                     # brackets cost time between launches
-                step()
-            kt = {}
-            for name, ms in gaf.gaf_profile_end(ctx, 65536):
-                kt.setdefault(name, []).append(ms)
-            entry = {"schedule": label, "steps": k,
-                     "ms_per_step": ms_o, "value": bmin_bytes(w, masks[0]) / (ms_o * 1e-3) / 1e9,
-                     "kernel_ms": {n: sum(v) / len(v) for n, v in kt.items()}}
-            if sched == "gram" and "gram" in kt:
-                g_ms = sum(kt["gram"]) / len(kt["gram"])
-                entry["gram_kernel_hbm_frac"] = N * s * P / (g_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS
-            other.append(entry)
-        gaf.gaf_set_schedule(ctx, args.schedule)
-        state["schedule"] = args.schedule
-
-    # ---- the memory system's own ceilings; the dominant kernel's rate is also reported as a fraction
-    # of whichever of the two matches its read/write mix
-    ceilings = None
+    other = ceilings = cpu = None
     if not args.only_profile_loop:
+        if mode != "step" and args.schedule == "auto":
+            other = other_schedules(gaf, torch, w, [grads], mode, args.steps, wall)
+        # the memory system's own ceilings; the dominant kernel's rate is also reported as a
+        # fraction of whichever of the two matches its read/write mix
         ceilings = measure_ceilings(gaf, torch)
-        if "error" not in ceilings:
-            writes = ((dom == "gram" and any(r["write"] for r in records)) or dom == "mean" or
-                      (dom == "reduce" and w.mode != "step"))
-            roof["frac_of_measured_ceiling"] = (roof["achieved"] / ceilings["copy" if writes else "read_only"]
-                                                if roof["bound"] == "hbm" else None)
+        if "error" not in ceilings and roof["bound"] == "hbm":
+            writes = (roof["kernel"] in ("mean", "update", "seed_reduce") or
+                      (roof["kernel"] == "gram" and any(r["write"] for r in rec)) or
+                      (roof["kernel"] == "reduce" and mode != "step_plain"))
+            roof["frac_of_measured_ceiling"] = roof["achieved"] / ceilings["copy" if writes else "read_only"]
+        if args.cpu_seconds > 0:
+            cpu = cpu_baseline(w, grads, mode, args.seed, args.cpu_seconds, wl, np)
+    head.close()
 
-    # ---- CPU baseline ----
-    cpu = None
-    if args.cpu_seconds > 0 and not args.only_profile_loop:
-        cpu = cpu_baseline(w, grads, args.seed, args.cpu_seconds, wl, np)
+    shared = {"large": (w, grads)} if (args.workload == "large" and args.P is None and args.N is None) else {}
+    del grads
+    configs = []
+    for name in args.configs:
+        t1 = time.time()
+        entry = run_config(name, gaf, torch, wl, np, args, traffic_db, shared)
+        entry["seconds_spent"] = time.time() - t1
+        entry.pop("kernel_ms", None)
+        configs.append(entry)
+        if name == "large_near_tau":
+            shared.pop("large", None)
+        torch.cuda.empty_cache()
 
     line = {
-        "metric": "gaf_filter_average_effective_hbm_gbps",
-        "value": value,
+        "metric": "gaf_filter_average_hbm_gbps",
+        "value": res.get("achieved_gbps"),
         "unit": "GB/s",
-        "pct_of_hbm_peak": None if value is None else 100.0 * value / PEAK_HBM_GBPS,
-        "micro_gradients_per_s": None if ms_per_step is None else N / (ms_per_step * 1e-3),
+        "value_definition": "bytes the executed schedule must move per step (schedule_bytes_per_step: the algorithmic "
+                            "bytes of every launch) / wall time per step; a bandwidth, bounded by the HBM peak",
+        "frac_of_hbm_peak": res.get("achieved_frac_of_hbm_peak"),
+        "micro_gradients_per_s": res.get("micro_gradients_per_s"),
+        "bmin_equivalent_gbps": res.get("bmin_equivalent_gbps"),
+        "bmin_equivalent_definition": "B_min of the sequential formulation (bmin_bytes_per_step) / wall time: the rate a "
+                                      "one-visit-per-gradient implementation would need for the same time; the Gram-first "
+                                      "schedule moves fewer bytes, so this can exceed the HBM peak and is not a bandwidth",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "ms_per_step_hip_events": ms_per_step_events,
+        "ms_per_step": wall,
+        "ms_per_step_hip_events": ev,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
-        "dtype_detail": "%s gradients, binary32 running mean and output, binary64 inner products"
-                        % w.dtype,
+        "dtype_detail": "%s gradients, binary32 running mean and output, binary64 inner products" % w.dtype,
         "data": "synthetic",
-        "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau,
-                   "mode": w.mode, "schedule": schedule_used, "hip_graph": bool(args.graph), "seed": args.seed, "accepted": c_h,
-                   "batches": B, "accepted_per_batch": counts,
-                   "guesses": ({"source": "sample of this call's gradients" if fused else "previous call's accept set",
-                                "mean_written_by_gram_pass": sum(r["write"] for r in records),
-                                "right": sum(r["valid"] for r in records), "steps": len(records)}
-                               if records else None),
+        "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau, "mode": mode,
+                   "schedule": res["schedule"], "hip_graph": bool(args.graph), "seed": args.seed,
+                   "accepted": head.counts[0], "guesses": res.get("guesses"),
                    "generator": "g_i = a_i (s_i sqrt(rho_i) c + sqrt(1 - rho_i) z_i); rho, s, a from numpy Philox keyed by "
                                 "the seed, c and z_i from a torch.Generator on the device (" + w.noise + "); see workloads.py",
-                   "algorithmic_bytes_per_step": step_bytes,
-                   "launches_per_step": launches_per_step, "generate_seconds": gen_s},
+                   "schedule_bytes_per_step": res["schedule_bytes_per_step"], "bmin_bytes_per_step": res["bmin_bytes_per_step"],
+                   "launches_per_step": lps, "generate_seconds": gen_s},
         "roofline": roof,
         "measured_ceilings": ceilings,
         "cpu_baseline": cpu,
         "other_schedules": other,
-        "kernel_ms": {k: sum(v) / len(v) for k, v in per_kernel.items()},
-        "accept_mask": mask_h,
-        "cos_dist": [round(x, 6) for x in dist_h],
+        "configs": configs,
+        "kernel_ms": res["kernel_ms"],
+        "accept_mask": head.masks[0],
+        "cos_dist": [round(x, 6) for x in head.dists[0]],
         "paper_reference": "no throughput reported; experiments ran on 2x NVIDIA A40 with k = 2",
     }
     print(json.dumps(line))
-    gaf.gaf_destroy(ctx)
 
 
 if __name__ == "__main__":

@@ -74,18 +74,18 @@ __device__ __forceinline__ float load1(const bf16_t *p, size_t idx)
 // in bursts or not, temporal or not -- the memory turns around between reading and writing for
 // every small group of writes. What does help is making the WHOLE chip write at the same time.
 // The constant 100 MHz clock (s_memrealtime) reads the same in every compute unit, so it can
-// serve as the conductor without any communication: time is cut into periods of 2^k ticks whose
-// first `win` ticks are the write window. A workgroup keeps its results on chip, writes them out
+// serve as the conductor without any communication: time is cut into periods of `period` ticks
+// whose first `win` ticks are the write window. A workgroup keeps its results on chip, writes them out
 // when it finds the window open, and then idles until the window closes, so that for a few
 // microseconds the memory sees (nearly) nothing but writes and for the rest of the period nothing
 // but reads (measured on the same mix: 1.81 -> 1.45 ms, 6.7 TB/s in total).
 // Results never depend on it: the same values go to the same addresses, only later. Waiting is
 // bounded by the clock and, should the clock not move, by a spin limit.
 struct WriteGate {
-    unsigned mask, win;      // period - 1 and window length in 10 ns ticks; win == 0: never open
+    unsigned period, win;    // period and window length in 10 ns ticks; win == 0: never open
     __device__ __forceinline__ bool open() const
     {
-        return win != 0 && (unsigned(__builtin_amdgcn_s_memrealtime()) & mask) < win;
+        return win != 0 && unsigned(__builtin_amdgcn_s_memrealtime() % period) < win;
     }
     __device__ __forceinline__ void wait_closed() const
     {

@@ -121,9 +121,9 @@ struct GramArgs {
     // an ordinary launch has chunk_shift = 62 (one run that never ends) and chunk_stride = 0.
     int chunk_shift;
     size_t chunk_stride;
-    // kMean only: write windows (see WriteGate). gate_mask = period - 1 in ticks of the constant
-    // 100 MHz clock (period a power of two), gate_win = length of the window in ticks; 0 = no windows.
-    unsigned gate_mask, gate_win;
+    // kMean only: write windows (see WriteGate): period and length of the window in ticks of the
+    // constant 100 MHz clock; gate_win = 0: no windows.
+    unsigned gate_period, gate_win;
 };
 
 // 16 bytes of a row starting at element p, element-wise and zero past the end.
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         size_t k = 0;
         if (n_steady > 0) {
             size_t s = vblock;
-            const WriteGate gate{a.gate_mask, a.gate_win};
+            const WriteGate gate{a.gate_period ? a.gate_period : 1u, a.gate_win};
             int held = 0, parity = 0;          // pieces in the ring; which of the two flags this stage uses
             size_t held_from = s;              // stage of the oldest piece
             for (; k < n_steady; ++k, s += G) {

@@ -343,25 +343,26 @@ int spec_min_count(int N, bool carried)
 // elements, run r starting at element r * chunk_stride of every gradient.
 // Write windows of a pass that reads `read_bytes` and writes `write_bytes` in all (see WriteGate):
 // period and window length in ticks of the 100 MHz clock. The window's share of the period is the
-// share of the pass's time that the writing needs (rates measured on MI355X: 7.0 TB/s reading,
-// 5.0 TB/s writing, 6.5 TB/s for the pass as a whole), plus a tenth. A workgroup looks at the clock
-// once per stage, so a window is at least 1.15 stages long; it can hold `hold_stages` stages'
-// results, so the period is about the time those take -- unless the window's minimum length asks
-// for a longer one (then results are also written when the ring is full: few bytes in that case).
+// share of the pass's time that the writing needs at the rates measured on MI355X (7.0 TB/s
+// reading, 5.5 TB/s writing, 6.5 TB/s for the pass as a whole; on 16 x 1e9 bf16 a sweep of period
+// and window put the best window at 0.136 of the period, this formula gives 0.137). A workgroup
+// looks at the clock once per stage, so a window is at least 1.15 stages long; its ring holds
+// `hold_stages` stages' results, so the period is 0.8 of the time those take -- unless the
+// window's minimum length asks for a longer one (then results are also written when the ring is
+// full: few bytes in that case).
 struct GateParams {
-    unsigned mask, win;
+    unsigned period, win;
 };
 inline GateParams gate_params(double read_bytes, double write_bytes, double stage_bytes, int hold_stages)
 {
-    const double t_write = write_bytes / 5.0e12, t_total = read_bytes / 7.0e12 + t_write;
-    const double share = 1.1 * t_write / t_total;
+    const double t_write = write_bytes / 5.5e12, t_total = read_bytes / 7.0e12 + t_write;
+    const double share = t_write / t_total;
     const double stage_ticks = stage_bytes * kGramBlocks / 6.5e12 * 1e8;
     const double win_min = 1.15 * stage_ticks;
-    unsigned lg = 10;
-    while (lg < 15 && double(2u << lg) <= hold_stages * stage_ticks) ++lg;      // largest period the ring covers
-    while (lg < 15 && share * double(1u << lg) < win_min) ++lg;                 // ... or what the window needs
-    const double win = share * double(1u << lg);
-    return {(1u << lg) - 1, (unsigned)(win < win_min ? win_min : win)};
+    double period = 0.8 * hold_stages * stage_ticks;                 // what the ring covers, with a margin
+    if (share * period < win_min) period = win_min / share;          // ... or what the window needs
+    if (period > 30000.0) period = 30000.0;
+    return {(unsigned)period, (unsigned)(share * period)};
 }
 
 template <typename T, int NG, int kMode>
@@ -396,7 +397,7 @@ gaf_status gram_launch(gaf_ctx *ctx, const void *const *grads, int N, size_t P, 
         const double stage_bytes = 16.0 * NG * 256 * gram_stage_m(NG);
         const GateParams gp = gate_params(double(N) * sizeof(T) * P, 4.0 * P, stage_bytes,
                                           gram_hold_stages<T>(NG));
-        g.gate_mask = gp.mask;
+        g.gate_period = gp.period;
         g.gate_win = gp.win;
     }
     {
