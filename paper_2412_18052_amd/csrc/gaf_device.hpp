@@ -83,11 +83,25 @@ __device__ __forceinline__ float load1(const bf16_t *p, size_t idx)
 // bounded by the clock and, should the clock not move, by a spin limit.
 struct WriteGate {
     unsigned period, win;    // period and window length in 10 ns ticks; win == 0: never open
-    __device__ __forceinline__ bool open() const
+    unsigned base;           // start of the period the last look at the clock fell into
+    // (the low 32 bits of the clock are enough: they wrap every 43 s, which costs one odd period)
+    __device__ __forceinline__ WriteGate(unsigned period_, unsigned win_) : period(period_ ? period_ : 1u), win(win_)
     {
-        return win != 0 && unsigned(__builtin_amdgcn_s_memrealtime() % period) < win;
+        const unsigned t = unsigned(__builtin_amdgcn_s_memrealtime());
+        base = t - t % period;          // the one division; afterwards the period is tracked by subtraction
     }
-    __device__ __forceinline__ void wait_closed() const
+    __device__ __forceinline__ bool open()
+    {
+        if (win == 0) return false;
+        unsigned d = unsigned(__builtin_amdgcn_s_memrealtime()) - base;
+        if (d >= period) {
+            const unsigned n = d >= 2 * period ? d / period : 1u;      // more than a period since the last look: rare
+            base += n * period;
+            d -= n * period;
+        }
+        return d < win;
+    }
+    __device__ __forceinline__ void wait_closed()
     {
         for (int spin = 0; spin < 4096 && open(); ++spin) __builtin_amdgcn_s_sleep(4);
     }

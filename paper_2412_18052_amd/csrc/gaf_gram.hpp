@@ -161,20 +161,27 @@ __device__ __forceinline__ void gram_mma(const u32x4_t &x, const u32x4_t &y, flo
 // no preferred sign). hi*hi + hi*mid + mid*hi + mid*mid + hi*lo + lo*hi then
 // reproduces x*y to about 2^-23 relative -- binary32 product accuracy -- with six
 // bfloat16 MFMAs that together take 3/8 of the time of the binary32 MFMAs they
-// replace.
+// replace. Converted two values at a time (one packed conversion instruction per pair).
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void split3(const u32x4_t &w0, const u32x4_t &w1, bf16x8_t &hi, bf16x8_t &mid,
                                        bf16x8_t &lo)
 {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float x = __uint_as_float(e < 4 ? w0[e & 3] : w1[e & 3]);
-        const __bf16 h = (__bf16)x;
-        const float r1 = x - (float)h;
-        const __bf16 m = (__bf16)r1;
-        const float r2 = r1 - (float)m;
-        hi[e] = h;
-        mid[e] = m;
-        lo[e] = (__bf16)r2;
+    for (int e = 0; e < 8; e += 2) {
+        const f32x2_t x = {__uint_as_float(e < 4 ? w0[e & 3] : w1[e & 3]),
+                           __uint_as_float(e < 4 ? w0[(e + 1) & 3] : w1[(e + 1) & 3])};
+        const bf16x2_t h = __builtin_convertvector(x, bf16x2_t);
+        const f32x2_t r1 = x - __builtin_convertvector(h, f32x2_t);
+        const bf16x2_t m = __builtin_convertvector(r1, bf16x2_t);
+        const f32x2_t r2 = r1 - __builtin_convertvector(m, f32x2_t);
+        const bf16x2_t l = __builtin_convertvector(r2, bf16x2_t);
+        hi[e] = h[0];
+        hi[e + 1] = h[1];
+        mid[e] = m[0];
+        mid[e + 1] = m[1];
+        lo[e] = l[0];
+        lo[e + 1] = l[1];
     }
 }
 
@@ -341,27 +348,53 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     };
     auto compute = [&](int buf) {
         if (kSplit) {
+            // Group g + 1 is read and split (vector ALU) while the tiles whose later group is g are
+            // multiplied (matrix core): the tile list is ordered by later group, so the two streams
+            // of instructions are independent and can be issued side by side.
             static_assert(M % 2 == 0, "the split path consumes 32 columns per MFMA");
 #pragma unroll
             for (int c = 0; c < M / 2; ++c) {
                 bf16x8_t hi[NG], mid[NG], lo[NG];
-#pragma unroll
-                for (int g = 0; g < NG; ++g) {
+                auto fetch = [&](int g) {
                     const uint32_t *src = &stage[buf * kStageWords + (g * 16 + l16) * kRowWords +
                                                  wave * 16 * M + c * 32 + sub * 8];
                     split3(*reinterpret_cast<const u32x4_t *>(src), *reinterpret_cast<const u32x4_t *>(src + 4),
                            hi[g], mid[g], lo[g]);
-                }
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int ga = Tiles::ga(t), gb = Tiles::gb(t);
-                    mma_bf16(hi[ga], hi[gb], acc[t]);
-                    mma_bf16(hi[ga], mid[gb], acc[t]);
-                    mma_bf16(mid[ga], hi[gb], acc[t]);
-                    mma_bf16(mid[ga], mid[gb], acc[t]);
-                    mma_bf16(hi[ga], lo[gb], acc[t]);
-                    mma_bf16(lo[ga], hi[gb], acc[t]);
-                }
+                };
+                fetch(0);
+                // Phase g: the tiles whose later group is g (6 (g + 1) MFMAs), with the split of
+                // group g + 1 (about 48 vector-ALU instructions) dealt out between them; left to
+                // itself the scheduler puts all splits first and all MFMAs behind them, and the two
+                // pipes take turns instead of running side by side.
+#define GAF_GRAM_PHASE(g)                                                                         \
+    if (g < NG) {                                                                                 \
+        if (g + 1 < NG) fetch(g + 1);                                                             \
+        _Pragma("unroll") for (int t = 0; t < NT; ++t)                                            \
+        {                                                                                         \
+            const int ga = Tiles::ga(t), gb = Tiles::gb(t);                                       \
+            if (kMode == kFull ? gb != g : (g != NG - 1)) continue;                               \
+            mma_bf16(hi[ga], hi[gb], acc[t]);                                                     \
+            mma_bf16(hi[ga], mid[gb], acc[t]);                                                    \
+            mma_bf16(mid[ga], hi[gb], acc[t]);                                                    \
+            mma_bf16(mid[ga], mid[gb], acc[t]);                                                   \
+            mma_bf16(hi[ga], lo[gb], acc[t]);                                                     \
+            mma_bf16(lo[ga], hi[gb], acc[t]);                                                     \
+        }                                                                                         \
+        if (kMode == kFull && g + 1 < NG) {                                                       \
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                    \
+            _Pragma("unroll") for (int i = 0; i < 6 * (g + 1); ++i)                               \
+            {                                                                                     \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                \
+                __builtin_amdgcn_sched_group_barrier(0x002, (48 + 6 * (g + 1) - 1) / (6 * (g + 1)), 0); \
+            }                                                                                     \
+        }                                                                                         \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
+    }
+                GAF_GRAM_PHASE(0)
+                GAF_GRAM_PHASE(1)
+                GAF_GRAM_PHASE(2)
+                GAF_GRAM_PHASE(3)
+#undef GAF_GRAM_PHASE
             }
             return;
         }
@@ -379,40 +412,49 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         }
     };
     // Eq. 5 over the guessed accept set for the stage in buffer `buf`: a thread adds, for each of
-    // its four columns, the guessed rows in visiting order, four rows' reads issued at once; rows
-    // past the guess read the zero row, and adding +0 changes no bit of a sum that started from +0.
+    // its four columns, the guessed rows in visiting order, a batch of rows' reads issued at once;
+    // rows past the guess read the zero row, and adding +0 changes no bit of a sum that started
+    // from +0.
     const float inv_c = 1.0f / (float)(c_pred > 0 ? c_pred : 1);
+    constexpr int kMeanBatch = 8;      // rows read at once
     auto mean_piece = [&](int buf) {
         f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
         if (tid < kQuads) {
             const uint32_t *src = &stage[buf * kStageWords + (sizeof(T) == 4 ? 4 : 2) * tid];
             typedef int32_t i32x4_t __attribute__((ext_vector_type(4)));
-            for (int k0 = 0; k0 < c_pred; k0 += 4) {      // uniform trip count
-                const i32x4_t off = *reinterpret_cast<const i32x4_t *>(&pred_off[k0]);
-                int o[4];
+            for (int k0 = 0; k0 < c_pred; k0 += 16) {      // uniform trip count
+                // sixteen offsets in one go (one LDS round trip), then the rows in batches
+                i32x4_t offv[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) o[k] = __builtin_amdgcn_readfirstlane(off[k]);
-                if (sizeof(T) == 4) {
-                    u32x4_t w[4];
+                for (int q = 0; q < 4; ++q) offv[q] = *reinterpret_cast<const i32x4_t *>(&pred_off[k0 + 4 * q]);
+                int o[16];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) w[k] = *reinterpret_cast<const u32x4_t *>(src + o[k]);
+                for (int k = 0; k < 16; ++k) o[k] = __builtin_amdgcn_readfirstlane(offv[k / 4][k % 4]);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        sum.x += __uint_as_float(w[k].x);
-                        sum.y += __uint_as_float(w[k].y);
-                        sum.z += __uint_as_float(w[k].z);
-                        sum.w += __uint_as_float(w[k].w);
-                    }
-                } else {
-                    u32x2_t w[4];
+                for (int b0 = 0; b0 < 16; b0 += kMeanBatch) {
+                    if (k0 + b0 >= c_pred) break;          // uniform
+                    if (sizeof(T) == 4) {
+                        u32x4_t w[kMeanBatch];
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) w[k] = *reinterpret_cast<const u32x2_t *>(src + o[k]);
+                        for (int k = 0; k < kMeanBatch; ++k) w[k] = *reinterpret_cast<const u32x4_t *>(src + o[b0 + k]);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        sum.x += __uint_as_float(w[k].x << 16);
-                        sum.y += __uint_as_float(w[k].x & 0xffff0000u);
-                        sum.z += __uint_as_float(w[k].y << 16);
-                        sum.w += __uint_as_float(w[k].y & 0xffff0000u);
+                        for (int k = 0; k < kMeanBatch; ++k) {
+                            sum.x += __uint_as_float(w[k].x);
+                            sum.y += __uint_as_float(w[k].y);
+                            sum.z += __uint_as_float(w[k].z);
+                            sum.w += __uint_as_float(w[k].w);
+                        }
+                    } else {
+                        u32x2_t w[kMeanBatch];
+#pragma unroll
+                        for (int k = 0; k < kMeanBatch; ++k) w[k] = *reinterpret_cast<const u32x2_t *>(src + o[b0 + k]);
+#pragma unroll
+                        for (int k = 0; k < kMeanBatch; ++k) {
+                            sum.x += __uint_as_float(w[k].x << 16);
+                            sum.y += __uint_as_float(w[k].x & 0xffff0000u);
+                            sum.z += __uint_as_float(w[k].y << 16);
+                            sum.w += __uint_as_float(w[k].y & 0xffff0000u);
+                        }
                     }
                 }
             }
@@ -470,7 +512,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         size_t k = 0;
         if (n_steady > 0) {
             size_t s = vblock;
-            const WriteGate gate{a.gate_period ? a.gate_period : 1u, a.gate_win};
+            WriteGate gate(a.gate_period, a.gate_win);
             int held = 0, parity = 0;          // pieces in the ring; which of the two flags this stage uses
             size_t held_from = s;              // stage of the oldest piece
             for (; k < n_steady; ++k, s += G) {
