@@ -37,7 +37,17 @@
  *     gradients in binary32 (Eq. 4 does not change when one argument is
  *     rescaled, so distances against the mean equal distances against the
  *     paper's running sum; the mean makes the division of Eq. 5 implicit).
- *     Inner products and norms are accumulated in binary64.
+ *     Inner products and norms: the sequential passes and batches of up to 8
+ *     gradients add exact products of the inputs in binary64. Larger batches on
+ *     the Gram-first schedule use the matrix cores: products exact (bfloat16
+ *     inputs) or to 2^-23 relative (binary32 inputs, three-way bfloat16 split),
+ *     summed in binary32 inside the matrix core over at most 8 stages of 128 to
+ *     512 columns, then added into binary64 totals. A binary32 sum of n terms
+ *     rounds by at most n 2^-24 of the sum of the terms' magnitudes, and those
+ *     roundings are not systematic, so an inner product is off by about
+ *     1e-7 |x||y| at worst and far less on long vectors; the reported
+ *     distances stay within 1e-6 of the binary64 value (tested down to 2500
+ *     columns with all rows correlated at 0.98).
  *   - Ties: D_i == tau accepts. A zero-norm operand gives D_i = 1 by
  *     definition. A NaN distance (NaN or Inf in g_i) is stored as NaN and
  *     rejects g_i; the aggregate is left bit-for-bit unchanged.
@@ -63,7 +73,7 @@ typedef enum {
     GAF_OK = 0,
     GAF_EINVAL = 1,       /* NULL where a pointer is required, N < 1, P == 0, sizes beyond the context's */
     GAF_EALIGN = 2,       /* a DEVICE vector pointer is not 16-byte aligned */
-    GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace */
+    GAF_ENOMEM = 3,       /* gaf_create could not allocate its workspace (or a call its small host-side table) */
     GAF_EHIP = 4,         /* a HIP runtime call or kernel launch failed */
     GAF_EUNSUPPORTED = 5, /* unknown dtype, or N outside the range of the requested form */
     GAF_EDEVICE = 6,      /* the context's device is not the calling thread's current device */
@@ -284,7 +294,7 @@ gaf_status gaf_aggregate_with_matrix(gaf_ctx *ctx, const void *const *grads, int
 
 /*
  * Order-indifferent variant the paper sketches for the filter's dependence on
- * the seed (Sec. 3.1, last paragraph; "Order Indifference" under future
+ * the seed (Sec. 3.1, last paragraph; the order-indifference item under future
  * research): every micro-gradient takes a turn as the seed, the others being
  * visited in ring order behind it (s, s+1, .., N-1, 0, .., s-1), and the run
  * with the largest agreement is kept. Readings taken: agreement = number of
@@ -323,8 +333,9 @@ gaf_status gaf_aggregate_sgd(gaf_ctx *ctx, const void *const *grads, int N, size
                              int32_t *count, void *stream);
 
 /*
- * Bucketed filtering ("cosine distance to buckets at a time", future research):
- * the parameter vector is cut into B contiguous buckets -- layers, or the
+ * Bucketed filtering (the per-bucket form of the distance that the paper lists
+ * under future research, as a way to save memory and computation): the
+ * parameter vector is cut into B contiguous buckets -- layers, or the
  * buckets of a gradient exchange -- and Algorithm 1 runs independently inside
  * each, with its own mask, distances and count.
  *   bucket_offsets  HOST array of B+1 element offsets, [0] = 0, [B] = P,

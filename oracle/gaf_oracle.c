@@ -283,7 +283,7 @@ int oracle_sgd_step(double *theta, double *v, const double *g_gaf, int32_t c, si
 }
 
 /*
- * Bucketed GAF ("cosine distance to buckets at a time", future research): the
+ * Bucketed GAF (the per-bucket form of the distance listed under future research): the
  * parameter vector is cut into B contiguous buckets [off[b], off[b+1]) and
  * Algorithm 1 runs independently inside each bucket. mask and dist are B x N
  * row-major, count has B entries, out has P entries.

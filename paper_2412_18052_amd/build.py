@@ -11,7 +11,7 @@ HEADERS = [os.path.join(CSRC, h) for h in ("gaf_device.hpp", "gaf_pass.hpp", "ga
     os.path.join(os.path.dirname(HERE), "include", "gaf.h")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off", "-Wall", "-Wno-unused-command-line-argument",
 ]

@@ -10,7 +10,9 @@
 // accepted gradients plus one write of the result (mean_kernel, Eq. 5) --
 // instead of one read of the aggregate per visit and a rewrite per acceptance.
 // Same mask, distances and macro-gradient as the sequential schedule up to
-// rounding; the distances here come from exact-product binary64 sums.
+// rounding. For batches of up to 8 gradients the inner products are binary64 sums
+// of exact products; for larger ones they come from the matrix cores (binary32
+// sums over at most 8 stages, then binary64: about 1e-7 relative at worst).
 //
 // The second read of the accepted gradients is only needed because the accept
 // set is unknown while the Gram pass has the data on chip. Where it pays, the

@@ -88,6 +88,7 @@ struct Timed {
     bool live;
     Timed(gaf_ctx *c, hipStream_t st, gaf_kernel_id id) : ctx(c), s(st), live(false)
     {
+        // (gaf_profile_begin reserved room for prof_cap records: no allocation, nothing to throw, here)
         if (!c->prof_on || static_cast<int>(c->prof_id.size()) >= c->prof_cap) return;
         hipEvent_t a, b;
         if (hipEventCreate(&a) != hipSuccess) return;
@@ -893,6 +894,7 @@ gaf_status static_context(gaf_ctx **out)
 
 }  // namespace
 
+#pragma GCC visibility push(default)
 extern "C" {
 
 const char *gaf_strerror(gaf_status status)
@@ -988,6 +990,13 @@ gaf_status gaf_profile_begin(gaf_ctx *ctx, int max_launches)
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     ctx->prof_ev.clear();
     ctx->prof_id.clear();
+    try {
+        ctx->prof_ev.reserve(2 * static_cast<size_t>(max_launches));
+        ctx->prof_id.reserve(static_cast<size_t>(max_launches));
+    } catch (...) {
+        ctx->prof_on = false;
+        return GAF_ENOMEM;
+    }
     ctx->prof_cap = max_launches;
     ctx->prof_on = true;
     return GAF_OK;
@@ -1135,15 +1144,16 @@ gaf_status gaf_aggregate_bucketed(gaf_ctx *ctx, const void *const *grads, int N,
                    : bucketed_seg_impl<bf16_t, false>(ctx, grads, N, tau, B, bucket_offsets, out, accept_mask, cos_dist, count, st);
     }
     const size_t es = dt == GAF_F32 ? 4 : 2;
-    std::vector<const void *> slice(static_cast<size_t>(N));
-    for (int b = 0; b < B; ++b) {
+    const void **slice = new (std::nothrow) const void *[static_cast<size_t>(N)];
+    if (!slice) return GAF_ENOMEM;
+    for (int b = 0; b < B && rc == GAF_OK; ++b) {
         const size_t lo = bucket_offsets[b], len = bucket_offsets[b + 1] - lo;
         for (int i = 0; i < N; ++i) slice[i] = static_cast<const char *>(grads[i]) + lo * es;
-        rc = aggregate_dispatch(ctx, slice.data(), N, len, dt, tau, out + lo, accept_mask + size_t(b) * N,
+        rc = aggregate_dispatch(ctx, slice, N, len, dt, tau, out + lo, accept_mask + size_t(b) * N,
                                 cos_dist + size_t(b) * N, count + b, static_cast<hipStream_t>(stream));
-        if (rc != GAF_OK) return rc;
     }
-    return GAF_OK;
+    delete[] slice;
+    return rc;
 }
 
 gaf_status gaf_set_schedule(gaf_ctx *ctx, gaf_schedule schedule)
@@ -1296,3 +1306,4 @@ gaf_status gaf_aggregate_static(const void *const *grads, int N, size_t P, gaf_d
 }
 
 }  // extern "C"
+#pragma GCC visibility pop

@@ -41,14 +41,15 @@ _lib = None
 
 
 def load(path=None):
-    """Load libgaf.so (building it with hipcc first if it has never been built)."""
+    """Load libgaf.so. The in-tree library is built first if it is missing or older than any of
+    its sources (a stale binary would silently run yesterday's kernels); a failing build raises."""
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or LIB_PATH
-    if not os.path.exists(path):
+    if path is None:
         from . import build as _build
-        _build.build(force=True)
+        _build.build(force=False)
+    path = path or LIB_PATH
     lib = ctypes.CDLL(path)
     c = ctypes
     lib.gaf_create.restype = c.c_int

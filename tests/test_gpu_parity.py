@@ -50,7 +50,15 @@ def check_against_oracle(res_gpu, res_oracle, dtype):
     assert int(count.item()) == o_count
     d = dist.cpu().numpy().astype(np.float64)
     assert np.max(np.abs(d - o_dist)) <= DIST_ATOL, (d, o_dist)
-    assert rel_l2(out.cpu().numpy(), o_out) <= OUT_RTOL[dtype]
+    out_h = out.cpu().numpy()
+    assert rel_l2(out_h, o_out) <= OUT_RTOL[dtype]
+    # Element by element as well (a relative L2 norm would not notice a few wrong elements or one
+    # wrong tile among thousands). Both the running mean and the masked mean add c <= N values in
+    # binary32: each element is off by at most about (c + 2) 2^-24 of the largest partial sum,
+    # which is of the size of the largest output; a wrong element is off by the size of an input.
+    bound = 8.0 * (len(o_mask) + 2) * 2.0 ** -24 * np.max(np.abs(o_out))
+    worst = np.max(np.abs(out_h.astype(np.float64) - o_out)) if out_h.size else 0.0
+    assert worst <= bound, (worst, bound)
 
 
 def run_aggregate(ctx, oracle, grads_host, tau, dtype="f32"):
@@ -675,7 +683,10 @@ def test_large_full_size(ctx, oracle):
     assert np.max(np.abs(dist.cpu().numpy().astype(np.float64) - ref[2][:6])) <= DIST_ATOL
 
 
-@pytest.mark.timeout(600)
+_FULL_MATRIX = {}
+
+
+@pytest.mark.timeout(900)
 def test_diagnostic_full_size(ctx, oracle):
     for seed in range(4):
         w, grads = wl.generate("diagnostic", seed, device="cuda")
@@ -695,15 +706,13 @@ def test_diagnostic_full_size(ctx, oracle):
     Dh = D.cpu().numpy().astype(np.float64)
     assert np.array_equal(Dh, Dh.T) and np.all(np.diag(Dh) == 0)
     assert Dh.min() >= 0 and Dh.max() <= 2
-    # sampled entries, one oracle evaluation of Eq. 4 each: all four tile kinds, far corners
-    pairs = [(0, 1), (0, 31), (0, 32), (0, 63), (31, 32), (5, 40), (17, 18), (33, 62), (62, 63),
-             (2, 0), (47, 16), (63, 31), (20, 52), (12, 44)]
-    host = {}
-    for i, j in pairs:
-        for k in (i, j):
-            if k not in host:
-                host[k] = wl.to_host_array(grads[k])
-        assert abs(Dh[i, j] - oracle.cosine_distance(host[i], host[j])) <= DIST_ATOL, (i, j)
+    # every one of the 2016 pairs against the oracle's matrix (all 64 gradients on the host: 32 GB;
+    # the oracle's pass over them is the slow part and is done once for both schedules)
+    key = (seed, w.P, w.N)
+    if key not in _FULL_MATRIX:
+        _FULL_MATRIX.clear()
+        _FULL_MATRIX[key] = oracle.pairwise([wl.to_host_array(g) for g in grads])[0]
+    assert np.max(np.abs(Dh - _FULL_MATRIX[key])) <= DIST_ATOL
     # row 0 against the sequential distances up to the first acceptance
     first = int(np.argmax(ref[1][1:])) + 1
     assert np.max(np.abs(Dh[0, 1:first + 1] - ref[2][1:first + 1])) <= DIST_ATOL

@@ -11,7 +11,7 @@ import torch
 from conftest import MARGIN, oracle_arrays
 from paper_2412_18052_amd import gaf
 from paper_2412_18052_amd import workloads as wl
-from test_gpu_parity import DIST_ATOL, OUT_RTOL, check_against_oracle, rel_l2
+from test_gpu_parity import DIST_ATOL, OUT_RTOL, _oracle_sequential_from_device, check_against_oracle, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -99,9 +99,9 @@ def long_ctxs():
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("k,N,P,dtype", long_cases())
-def test_random_long_vectors_guessing_changes_nothing(long_ctxs, k, N, P, dtype):
-    """Vectors long enough for the accept set to be guessed from a sample (too long for the oracle
-    at these batch sizes). One AUTO context lives through all cases, so its record of guesses,
+def test_random_long_vectors_guessing_changes_nothing(long_ctxs, oracle, k, N, P, dtype):
+    """Vectors long enough for the accept set to be guessed from a sample. One AUTO context lives
+    through all cases, so its record of guesses,
     backoff included, is in whatever state the earlier cases left. The first gradients behind the
     seed are built to sit within the sample's error of tau, so that guesses do go wrong. Whatever
     was guessed, the AUTO result must equal the two-pass schedule's bit for bit, and the
@@ -132,6 +132,17 @@ def test_random_long_vectors_guessing_changes_nothing(long_ctxs, k, N, P, dtype)
         records.append(gaf.gaf_fused_mean_record(auto))
         for x, y in zip(res, ref):
             assert torch.equal(x, y), (k, rep, records)
+    # the oracle, fed one gradient at a time: its mask up to the first distance that comes within
+    # 1e-3 of tau (from there on a rounding difference may legitimately decide otherwise), its
+    # distances up to that point, and everything if no distance comes that close
+    o_out, o_mask, o_dist, o_count = _oracle_sequential_from_device(oracle, grads, tau)
+    o_clear = np.abs(o_dist[1:] - np.float32(tau)) >= 1e-3
+    upto = N if o_clear.all() else 1 + int(np.argmin(o_clear))
+    assert ref[1].cpu().numpy()[:upto].tolist() == o_mask[:upto].tolist()
+    assert np.max(np.abs(ref[2].cpu().numpy().astype(np.float64)[:upto] - o_dist[:upto])) <= DIST_ATOL
+    if upto == N:
+        check_against_oracle(ref, (o_out, o_mask, o_dist, o_count), dtype)
+    del o_out
     d = ref[2].cpu().numpy().astype(np.float64)
     clear = np.abs(d - np.float32(tau)) >= 5e-4
     m_ref, m_seq = ref[1].cpu().numpy(), seq[1].cpu().numpy()
