@@ -481,9 +481,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
         if (tid < kQuads) hold[slot * kQuads + tid] = o;
     };
     // writes out the `n` held pieces, which belong to stages s0, s0 + G, ...
+    // (LDS reads in batches, so that the stores of a flush leave within a fraction of a window)
+    constexpr int kFlushBatch = 8;
     auto hold_flush = [&](int n, size_t s0) {
         if (tid < kQuads)
-            for (int j = 0; j < n; ++j) mean_store(hold[j * kQuads + tid], s0 + size_t(j) * G);
+            for (int j0 = 0; j0 < n; j0 += kFlushBatch) {
+                f32x4_t v[kFlushBatch];
+#pragma unroll
+                for (int j = 0; j < kFlushBatch; ++j) v[j] = hold[((j0 + j < n) ? j0 + j : j0) * kQuads + tid];
+#pragma unroll
+                for (int j = 0; j < kFlushBatch; ++j)
+                    if (j0 + j < n) mean_store(v[j], s0 + size_t(j0 + j) * G);
+            }
     };
     auto flush = [&]() {
 #pragma unroll
