@@ -55,6 +55,13 @@
  *   - Determinism: for a given (P, dtype) the launch shape and every summation
  *     order are fixed; no floating-point atomics are used. Repeating a call on
  *     the same inputs gives bit-identical outputs.
+ *   - Timing knob (no result depends on it): the Gram-first pass that also
+ *     writes the macro-gradient releases its stores in write windows of the
+ *     GPU's constant 100 MHz clock, so that the memory is not turned around
+ *     between reading and writing for every few KB. The environment variable
+ *     GAF_WRITE_WINDOWS, read once per process, is "0" to switch the windows
+ *     off or "PERIOD:WINDOW" (10 ns ticks, WINDOW < PERIOD) to fix them; left
+ *     unset, period and window follow from the read/write mix of the call.
  *   - Errors are returned as gaf_status; nothing is thrown across the ABI.
  *     On any status other than GAF_OK nothing was enqueued, except GAF_EHIP,
  *     which reports a failed launch part-way (outputs are then undefined).
