@@ -314,18 +314,18 @@ gaf_status step_lookahead_impl(gaf_ctx *ctx, float *accum, int32_t *count, const
     return launched();
 }
 
-// Smallest predicted accept count for which the Gram pass writes the mean itself. Mixing the
-// 4 P written bytes into the reading pass added 0.6 to 2.5 ms to the measured calls (batches of
-// 32 GB), nearly independent of the count c, while the stand-alone mean costs (c s + 4) P bytes
-// at about 5.85 TB/s; below these break-even counts (smallest c at which the whole call was
-// measured faster with the fused write, 32 GB batches) the stand-alone mean is the cheaper one
-// (by up to 15% of the call at c = 1).
+// Smallest predicted accept count for which the Gram pass writes the mean itself. Writing the
+// 4 P bytes from inside the reading pass (in write windows) added 0.9 to 1.2 ms to the measured
+// calls (batches of 32 GB), independent of the count c, while the stand-alone mean costs
+// (c s + 4) P bytes at about 5.9 TB/s; below these break-even counts (smallest c at which the
+// whole call was measured faster with the fused write, 32 GB batches) the stand-alone mean is the
+// cheaper one (by at most 7% of the call).
 // groups = 0 means the small-batch (N <= 8) kernel.
 template <typename T>
 constexpr int fused_min_count(int groups)
 {
-    constexpr int bf16_min[5] = {2, 5, 9, 8, 12};
-    constexpr int f32_min[5] = {1, 4, 8, 8, 7};
+    constexpr int bf16_min[5] = {2, 2, 2, 4, 6};
+    constexpr int f32_min[5] = {1, 2, 5, 4, 5};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
 // The same for a batch of N gradients. A guess carried over from the previous call is used on

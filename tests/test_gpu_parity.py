@@ -457,8 +457,8 @@ def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
     the mean of the guess. Here some gradients agree with the seed on the sampled elements and
     oppose it on the rest, so the guess is wrong and the stand-alone mean must take over; a
     second batch is twisted on a prefix instead and a third not at all (guess right). With the "few"
-    pattern only one gradient in five agrees with the seed: below a break-even accept count the
-    Gram pass leaves the mean to the stand-alone kernel even when the guess is right."""
+    pattern no gradient agrees with the seed: below a break-even accept count (two at these batch
+    sizes) the Gram pass leaves the mean to the stand-alone kernel even when the guess is right."""
     P = (1 << 26) + 12_345
     gen = torch.Generator(device="cuda").manual_seed(100 + N)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -467,7 +467,7 @@ def test_fused_mean_with_right_and_wrong_guess(ctx, oracle, N, dtype, pattern):
     sampled = (torch.arange(256, device="cuda")[:, None] * stride + torch.arange(run, device="cuda")[None, :]).reshape(-1)
     flip = torch.ones(P, device="cuda"); flip[sampled] = -1.0
     flip_prefix = torch.ones(P, device="cuda"); flip_prefix[: 1 << 22] = -1.0
-    signs = ([1, 1, -1, 1, -1] if pattern == "mixed" else [1, -1, -1, -1, -1]) * (N // 5)
+    signs = [1, 1, -1, 1, -1] * (N // 5) if pattern == "mixed" else [1] + [-1] * (N - 1)
     # twist "sample": on the sampled elements; "prefix": on the first 2^22 elements instead (one
     # atypical layer at the front: the spread-out sample must not be misled by it)
     for twist in ("sample", "prefix", None):
