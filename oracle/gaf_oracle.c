@@ -207,8 +207,8 @@ int oracle_gaf_pairwise(const void *const *grads, int N, size_t P, int dtype, do
 }
 
 /*
- * Order-indifferent variant (Sec. 3.1, last paragraph; "Order Indifference"
- * under future research): every micro-gradient acts as the seed in turn, the
+ * Order-indifferent variant (Sec. 3.1, last paragraph; the item on order
+ * indifference under future research): every micro-gradient acts as the seed in turn, the
  * others are visited in ring order behind it (s, s+1, .., N-1, 0, .., s-1),
  * and the run with the largest agreement is the one that is kept.
  * Readings: "agreement" = number of accepted gradients c; ties go to the

@@ -263,9 +263,10 @@ __host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlo
 // matrix-core Gram kernel for the idea); the plain filter visits in index order,
 // so adding the predicted rows in index order reproduces the stand-alone mean
 // kernel bit for bit.
-// kHalves = 2 (see the matrix-core Gram kernel): the workgroup is two halves of kBlock threads,
-// each a virtual workgroup of its own (`first`, `out` and the tiles belong to the calling half)
-// that share only a barrier per tile, which keeps the two from drifting apart.
+// kHalves = 2: the workgroup is two halves of kBlock threads, each a virtual workgroup of its
+// own (`first`, `out` and the tiles belong to the calling half) that share only a barrier per
+// tile, which keeps the two from drifting apart (two separate workgroups on a compute unit were
+// seen to finish far apart when the kernel also writes: the older one is served first).
 template <typename T, int N, bool kStream, bool kMean = false, int kHalves = 1>
 __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmallMaxN], size_t lo, size_t hi,
                                                  size_t first, size_t stride, double *out, size_t out_stride,
