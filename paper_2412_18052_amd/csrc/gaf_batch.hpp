@@ -159,6 +159,8 @@ __device__ __forceinline__ void filter_body(const double *gram, int N, float tau
             pred->penalty = penalty;
             pred->write = wrote ? 1 : 0;
             pred->valid = (wrote && same) ? 1 : 0;
+            if (pred->notify)
+                __hip_atomic_store(pred->notify, pred->valid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             pred->next_tile = 0;             // tile counter of the mean launch that follows
             if (carried) {
                 pred->n = N;

@@ -94,6 +94,9 @@ struct Prediction {
     int32_t penalty;   // backoff imposed by the next wrong guess: doubles per miss up to kSpecMaxPenalty,
                        // halves per hit; 0 = never used, treated as 1
     uint32_t next_tile;  // work counter of the mean launch after a guess (cleared by the verifying filter)
+    int32_t *notify;   // host memory the device can write, or null: receives `valid` of every verified guess,
+                       // so that the host can size the next call's mean launch for what is likely to come
+                       // (a hint only: no result depends on it). Set once when the context is created.
 };
 
 // Guess carried over from the previous call (carry_n = this call's N): is it usable, and does

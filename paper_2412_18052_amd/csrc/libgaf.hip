@@ -29,6 +29,8 @@ struct gaf_ctx {
     SeedWs *seed_ws;     // device, per-seed filter runs (order-indifferent variant)
     SegWs *seg_ws;       // device, per-bucket filter outcomes (bucketed filtering)
     Prediction *pred;    // device, accept set predicted from a sample (fused mean) and the record of earlier guesses
+    volatile int32_t *guess_note;   // pinned host memory (null in the context that allocates nothing): whether the
+                                    // last verified guess left the result in place, written by the device
     bool pred_reset;     // that record is to be cleared by the next call that guesses
     gaf_schedule schedule;
     // streaming with look-ahead: the gradient whose decision (in `st`) has not been applied yet
@@ -684,7 +686,12 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     {
         // long vectors after a guess: the launch may have nothing to do, so a bounded grid that
         // claims its tiles from a counter
-        m.claim_tiles = speculate && size_t(tile_blocks(P)) >= kMeanQueueMinTiles;
+        // ... unless the last guess the host has heard of did not leave the result in place (declined,
+        // wrong, or backing off): then the launch will most likely have all the work to do, and one
+        // workgroup per tile does that 8 % faster. The note may be a call or two old; either grid is
+        // correct whatever happens.
+        const bool expect_in_place = !ctx->guess_note || *ctx->guess_note != 0;
+        m.claim_tiles = speculate && expect_in_place && size_t(tile_blocks(P)) >= kMeanQueueMinTiles;
         const int nb = m.claim_tiles ? kMeanQueueBlocks : tile_blocks(P);
         Timed t(ctx, s, GAF_K_MEAN);
         if (opt.theta)
@@ -904,6 +911,7 @@ gaf_status static_context(gaf_ctx **out)
         c->seg_ws = reinterpret_cast<SegWs *>(base + kStOffSegWs);
         c->pred = reinterpret_cast<Prediction *>(base + kStOffPred);
         c->pred_reset = false;
+        c->guess_note = nullptr;
         c->pend_g = nullptr;
         c->schedule = GAF_SCHEDULE_AUTO;
         c->prof_on = false;
@@ -957,6 +965,7 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ctx->prof_cap = 0;
     ctx->schedule = GAF_SCHEDULE_AUTO;
     ctx->pred_reset = false;
+    ctx->guess_note = nullptr;
     ctx->pend_g = nullptr;
     const size_t gram_ws_bytes = sizeof(double) * size_t(kGramBlocks) * kGramMaxTiles * kGramTile;
     const size_t gram_full_bytes = sizeof(double) * size_t(max_N) * size_t(max_N);
@@ -973,6 +982,17 @@ gaf_status gaf_create(gaf_ctx **out_ctx, int device, size_t max_P, int max_N)
     ok = ok && hipMemset(ctx->st, 0, sizeof(State)) == hipSuccess;
     ok = ok && hipMemset(ctx->gram_full, 0, gram_full_bytes) == hipSuccess;
     ok = ok && hipMemset(ctx->pred, 0, sizeof(Prediction)) == hipSuccess;
+    {
+        // the note the verifying filter leaves for the host (pinned host memory, written by the device)
+        void *note = nullptr, *note_dev = nullptr;
+        ok = ok && hipHostMalloc(&note, 64, hipHostMallocDefault) == hipSuccess;
+        if (ok) {
+            ctx->guess_note = static_cast<volatile int32_t *>(note);
+            *ctx->guess_note = 1;
+            ok = hipHostGetDevicePointer(&note_dev, note, 0) == hipSuccess &&
+                 hipMemcpy(&ctx->pred->notify, &note_dev, sizeof note_dev, hipMemcpyHostToDevice) == hipSuccess;
+        }
+    }
     ok = ok && hipDeviceSynchronize() == hipSuccess;
     (void)hipSetDevice(prev);
     if (!ok) {
@@ -998,6 +1018,7 @@ gaf_status gaf_destroy(gaf_ctx *ctx)
     if (ctx->seed_ws) (void)hipFree(ctx->seed_ws);
     if (ctx->seg_ws) (void)hipFree(ctx->seg_ws);
     if (ctx->pred) (void)hipFree(ctx->pred);
+    if (ctx->guess_note) (void)hipHostFree(const_cast<int32_t *>(ctx->guess_note));
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     if (have_prev) (void)hipSetDevice(prev);
     delete ctx;
