@@ -12,7 +12,7 @@ point on the `large` batch, and for `large` with thresholds placed next to a dis
 
 Two byte counts per step, both stated:
   schedule bytes  what the executed schedule must move: the algorithmic bytes of every launch
-                  (table in the design doc). value = schedule bytes / time -- a real bandwidth, never
+                  (launch_bytes below). value = schedule bytes / time -- a real bandwidth, never
                   above the HBM peak.
   B_min           what the method as the paper states it (one visit per gradient) must move:
                   per visited gradient  s*P (read g_i) + 4*P (read the aggregate) + 4*P if accepted,
@@ -604,7 +604,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
-        "dtype_detail": "%s gradients, binary32 running mean and output, binary64 inner products" % w.dtype,
+        "dtype_detail": "%s gradients, binary32 running mean and output; inner products: binary64 sums of exact products (sequential passes, N <= 8), matrix cores with binary32 partial sums flushed to binary64 (larger batches)" % w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "N": N, "P": P, "input_dtype": w.dtype, "tau": w.tau, "mode": mode,
                    "schedule": res["schedule"], "hip_graph": bool(args.graph), "seed": args.seed,

@@ -20,7 +20,8 @@
  *   - Pointers marked DEVICE are addresses in the memory of the GPU the
  *     context was created on; pointers marked HOST are ordinary host memory.
  *     The library never takes ownership of a caller's buffer and never frees
- *     one. It allocates device memory only inside gaf_create.
+ *     one. It allocates device memory (and 64 bytes of pinned host memory)
+ *     only inside gaf_create.
  *   - Every call enqueues its kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and returns without waiting. Results
  *     are valid once the caller has synchronised that stream. Input buffers
