@@ -455,21 +455,29 @@ __global__ __launch_bounds__(kBlock) void gram_small_finalize_kernel(const doubl
 // matrix goes to LDS for the filter and to `gram` for whoever reads it later.
 constexpr int kFinalizeFilterMax = 8192;
 
-__global__ __launch_bounds__(kBlock) void finalize_filter_kernel(const double *partials, int nb, double *gram,
-                                                                 int N, float tau, State *st, uint8_t *mask,
-                                                                 float *cos_dist, int32_t *count,
-                                                                 int32_t *accepted_list, int spec,
-                                                                 Prediction *pred, int min_count)
+// The combine: red[kBlock] and g[kSmallMaxN^2] are the workgroup's LDS; `gram` (nullable) also
+// receives the matrix. Ends with a barrier: g is complete for every thread.
+__device__ __forceinline__ void finalize_partials(const double *partials, int nb, int N, double *red, double *g,
+                                                  double *gram)
 {
-    __shared__ double red[kBlock];
-    __shared__ double g[kSmallMaxN * kSmallMaxN];
     const int np = N * (N + 1) / 2;
     int S = 1;
     while (2 * S * np <= kBlock) S *= 2;
     const int pair = threadIdx.x / S, slice = threadIdx.x % S;
     double s = 0.0;
-    if (pair < np)
-        for (int b = slice; b < nb; b += S) s += partials[size_t(pair) * kMaxBlocks + b];
+    if (pair < np) {
+        // eight loads in flight at a time, added in index order (one memory round trip per eight
+        // values instead of one per value: this sum sits on the critical path of a 10 us call)
+        const double *src = partials + size_t(pair) * kMaxBlocks;
+        for (int b0 = slice; b0 < nb; b0 += 8 * S) {
+            double v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = b0 + k * S < nb ? src[b0 + k * S] : 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (b0 + k * S < nb) s += v[k];
+        }
+    }
     red[threadIdx.x] = s;
     for (int h = S / 2; h >= 1; h /= 2) {
         __syncthreads();
@@ -486,10 +494,23 @@ __global__ __launch_bounds__(kBlock) void finalize_filter_kernel(const double *p
         const int j = i + left;
         g[i * N + j] = v;
         g[j * N + i] = v;
-        gram[i * N + j] = v;
-        gram[j * N + i] = v;
+        if (gram) {
+            gram[i * N + j] = v;
+            gram[j * N + i] = v;
+        }
     }
     __syncthreads();
+}
+
+__global__ __launch_bounds__(kBlock) void finalize_filter_kernel(const double *partials, int nb, double *gram,
+                                                                 int N, float tau, State *st, uint8_t *mask,
+                                                                 float *cos_dist, int32_t *count,
+                                                                 int32_t *accepted_list, int spec,
+                                                                 Prediction *pred, int min_count)
+{
+    __shared__ double red[kBlock];
+    __shared__ double g[kSmallMaxN * kSmallMaxN];
+    finalize_partials(partials, nb, N, red, g, gram);
     if (threadIdx.x < 64)
         filter_body(g, N, tau, st, mask, cos_dist, count, accepted_list, spec, pred, min_count);
 }
@@ -646,6 +667,61 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
         if (t0 >= ntiles) return;       // every workgroup gets here once the tiles run out
         mean_range<T, kStream, kSgd>(a, table, list, c, 0, a.P, t0, 1, t0 + kMeanClaim);
     }
+}
+
+// Short vectors, small batches: combine, filter and mean in ONE launch behind the Gram kernel.
+// Every workgroup of the mean redoes the combine of the Gram kernel's partial sums and the
+// replay of Algorithm 1 for itself (same code and summation order as finalize_filter_kernel, so
+// all workgroups agree bit for bit with it and with each other), then takes its tile of Eq. 5;
+// workgroup 0 also publishes matrix, mask, distances, count and state. Saves a dependent launch
+// (6 to 9 us, a third of a call at P = 1e6); the host uses it only where the partial sums that
+// all the workgroups re-read stay a few MB in total.
+struct FilterOut {
+    double *gram;
+    State *st;
+    uint8_t *mask;
+    float *cos_dist;
+    int32_t *count;
+    int32_t *accepted_list;
+};
+
+template <typename T, bool kStream>
+__global__ __launch_bounds__(kBlock) void mean_filter_kernel(MeanArgs a, const double *partials, int nb, float tau,
+                                                             FilterOut o)
+{
+    __shared__ double red[kBlock];
+    __shared__ double g[kSmallMaxN * kSmallMaxN];
+    __shared__ const void *table[kBatchMaxN];
+    __shared__ int32_t list[kBatchMaxN];
+    __shared__ uint8_t l_mask[kSmallMaxN];
+    __shared__ float l_dist[kSmallMaxN];
+    __shared__ int l_count;
+    const int N = a.N;
+    if (threadIdx.x < kBatchMaxN) {
+        table[threadIdx.x] = a.rows[threadIdx.x];
+        list[threadIdx.x] = 0;
+    }
+    finalize_partials(partials, nb, N, red, g, blockIdx.x == 0 ? o.gram : nullptr);
+    if (threadIdx.x < 64) {
+        const int c = run_filter(g, N, 0, tau, l_mask, l_dist, list);
+        if (threadIdx.x == 0) l_count = c;
+    }
+    __syncthreads();
+    const int c = l_count;
+    if (blockIdx.x == 0) {
+        if (int(threadIdx.x) < N) {
+            o.mask[threadIdx.x] = l_mask[threadIdx.x];
+            o.cos_dist[threadIdx.x] = l_dist[threadIdx.x];
+        }
+        if (int(threadIdx.x) < c) o.accepted_list[threadIdx.x] = list[threadIdx.x];
+        if (threadIdx.x == 0) {
+            o.count[0] = c;
+            o.st->count = c;
+            o.st->accept = 0;
+            o.st->seed = 0;
+        }
+    }
+    mean_range<T, kStream, false>(a, table, list, c, 0, a.P, blockIdx.x, gridDim.x);
 }
 
 // ---- bucketed filtering in three launches (small batches) -------------------

@@ -564,6 +564,7 @@ constexpr size_t kCarryMinP = size_t(1) << 21;
 // 11.2 M elements drawn independently, the exact accept set of the previous call was never this
 // call's (0 of 20), so larger batches do not guess on short vectors.
 constexpr int kCarryN = 2;
+constexpr size_t kMergeMeanMaxBytes = size_t(8) << 20;   // partial sums re-read by all workgroups of a merged mean launch
 
 // Distance in elements between the starts of consecutive runs of the sample for vectors of
 // length P >= kSpecMinP: the runs spread over the whole vector, the last one ends inside it.
@@ -641,6 +642,10 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         if (rc != GAF_OK) return rc;
         gram = ctx->gram_full;
     }
+    // Short vectors: the mean launch does the combine and the filter as well, every workgroup for
+    // itself -- as long as what they all re-read of the Gram kernel's partial sums stays small.
+    const bool merge_mean = merge_nb != 0 && !speculate && !opt.theta && out &&
+                            size_t(tile_blocks(P)) * size_t(merge_nb) * (N * (N + 1) / 2) * sizeof(double) <= kMergeMeanMaxBytes;
     if (opt.best_seed) {
         {
             Timed t(ctx, s, GAF_K_FILTER);
@@ -652,6 +657,8 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
             seed_select_kernel<<<1, 64, 0, s>>>(ctx->seed_ws, N, ctx->st, mask, cos_dist, count,
                                                 opt.best_seed, ctx->accepted);
         }
+    } else if (merge_mean) {
+        // combine and filter ride in the mean launch below
     } else {
         const int spec = !speculate ? kSpecNone : carried ? kSpecVerifyCarried : kSpecVerify;
         Timed t(ctx, s, GAF_K_FILTER);
@@ -694,7 +701,10 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         m.claim_tiles = speculate && expect_in_place && size_t(tile_blocks(P)) >= kMeanQueueMinTiles;
         const int nb = m.claim_tiles ? kMeanQueueBlocks : tile_blocks(P);
         Timed t(ctx, s, GAF_K_MEAN);
-        if (opt.theta)
+        if (merge_mean)
+            mean_filter_kernel<T, kStream><<<nb, kBlock, 0, s>>>(
+                m, ctx->gram_ws, merge_nb, tau, FilterOut{ctx->gram_full, ctx->st, mask, cos_dist, count, ctx->accepted});
+        else if (opt.theta)
             mean_kernel<T, kStream, true><<<nb, kBlock, 0, s>>>(m);
         else
             mean_kernel<T, kStream, false><<<nb, kBlock, 0, s>>>(m);
