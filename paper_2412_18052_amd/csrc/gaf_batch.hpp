@@ -675,7 +675,9 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(MeanArgs a)
 // all workgroups agree bit for bit with it and with each other), then takes its tile of Eq. 5;
 // workgroup 0 also publishes matrix, mask, distances, count and state. Saves a dependent launch
 // (6 to 9 us, a third of a call at P = 1e6); the host uses it only where the partial sums that
-// all the workgroups re-read stay a few MB in total.
+// all the workgroups re-read stay a few MB in total. With nb == 0 the matrix has been combined
+// by a launch of its own and only the replay is redone per workgroup (small batches of any
+// length below the guessing threshold: still one launch fewer).
 struct FilterOut {
     double *gram;
     State *st;
@@ -701,7 +703,12 @@ __global__ __launch_bounds__(kBlock) void mean_filter_kernel(MeanArgs a, const d
         table[threadIdx.x] = a.rows[threadIdx.x];
         list[threadIdx.x] = 0;
     }
-    finalize_partials(partials, nb, N, red, g, blockIdx.x == 0 ? o.gram : nullptr);
+    if (nb > 0) {
+        finalize_partials(partials, nb, N, red, g, blockIdx.x == 0 ? o.gram : nullptr);
+    } else {                                   // the matrix is already combined: o.gram is the input
+        if (int(threadIdx.x) < N * N) g[threadIdx.x] = o.gram[threadIdx.x];
+        __syncthreads();
+    }
     if (threadIdx.x < 64) {
         const int c = run_filter(g, N, 0, tau, l_mask, l_dist, list);
         if (threadIdx.x == 0) l_count = c;

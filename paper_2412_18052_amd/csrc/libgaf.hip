@@ -646,6 +646,8 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
     // itself -- as long as what they all re-read of the Gram kernel's partial sums stays small.
     const bool merge_mean = merge_nb != 0 && !speculate && !opt.theta && out &&
                             size_t(tile_blocks(P)) * size_t(merge_nb) * (N * (N + 1) / 2) * sizeof(double) <= kMergeMeanMaxBytes;
+    // ... and otherwise, for small batches, at least the filter replay (from the combined matrix)
+    const bool merge_replay = !merge_mean && small && !speculate && !opt.theta && !opt.best_seed && out;
     if (opt.best_seed) {
         {
             Timed t(ctx, s, GAF_K_FILTER);
@@ -657,8 +659,8 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
             seed_select_kernel<<<1, 64, 0, s>>>(ctx->seed_ws, N, ctx->st, mask, cos_dist, count,
                                                 opt.best_seed, ctx->accepted);
         }
-    } else if (merge_mean) {
-        // combine and filter ride in the mean launch below
+    } else if (merge_mean || (merge_replay && !merge_nb)) {
+        // combine and filter, or the filter alone, ride in the mean launch below
     } else {
         const int spec = !speculate ? kSpecNone : carried ? kSpecVerifyCarried : kSpecVerify;
         Timed t(ctx, s, GAF_K_FILTER);
@@ -704,6 +706,10 @@ gaf_status aggregate_gram_impl(gaf_ctx *ctx, const void *const *grads, int N, si
         if (merge_mean)
             mean_filter_kernel<T, kStream><<<nb, kBlock, 0, s>>>(
                 m, ctx->gram_ws, merge_nb, tau, FilterOut{ctx->gram_full, ctx->st, mask, cos_dist, count, ctx->accepted});
+        else if (merge_replay && !merge_nb)
+            mean_filter_kernel<T, kStream><<<nb, kBlock, 0, s>>>(
+                m, nullptr, 0, tau,
+                FilterOut{const_cast<double *>(gram), ctx->st, mask, cos_dist, count, ctx->accepted});
         else if (opt.theta)
             mean_kernel<T, kStream, true><<<nb, kBlock, 0, s>>>(m);
         else
