@@ -21,8 +21,8 @@
 //   quarter of the rows, stores its 16-byte pieces to LDS (row stride padded by
 //   16 bytes: conflict-free), and after one barrier reads back, for EVERY row,
 //   its own quarter of the stage's columns in matrix-core layout.
-// Two LDS stages alternate; the global loads of stage k+1 are issued before the
-// MFMAs of stage k. Tiles accumulate in binary32 inside the matrix core and are
+// Two LDS stages alternate (one, with a second barrier, in the kernels that also write
+// the mean); the global loads of stage k+1 are issued before the MFMAs of stage k. Tiles accumulate in binary32 inside the matrix core and are
 // flushed into binary64 registers every kGramFlush stages.
 #pragma once
 #include <type_traits>
@@ -209,12 +209,17 @@ constexpr int kLdsPerBlock = 79 * 1024;   // bytes of LDS a workgroup may use: t
 
 // Geometry of a writing (kMean) kernel's LDS, by element size and number of row groups: words per
 // stage buffer (16 NG rows and the zero row, each padded), bytes of one stage's piece of the mean,
-// and how many such pieces the ring behind the two stage buffers holds.
+// and how many such pieces the ring behind the stage buffer holds.
 __host__ __device__ constexpr int gram_mean_stage_words(int ng) { return (16 * ng + 1) * (64 * gram_stage_m(ng) + kGramPad); }
 __host__ __device__ constexpr int gram_piece_bytes(int elem_bytes, int ng) { return 256 * gram_stage_m(ng) / elem_bytes * 4; }
+// (A writing kernel stages through ONE LDS buffer -- a second barrier per stage instead of a second
+// buffer -- so that the ring gets the space: with 64 rows two buffers would leave it 12 KB, far
+// less than a write window's worth. Measured against two buffers: 64 x 2.5e8 bf16 5.87 -> 5.33 ms,
+// 64 x 1.24e8 binary32 5.86 -> 5.77, 32 x 5e8 bf16 5.44 -> 5.34, 16 x 1e9 bf16 5.66 -> 5.60.)
+__host__ __device__ constexpr int gram_mean_bufs(int) { return 1; }
 __host__ __device__ constexpr int gram_hold_stages_for(int elem_bytes, int ng)
 {
-    const int n = (kLdsPerBlock - 2 * gram_mean_stage_words(ng) * 4) / gram_piece_bytes(elem_bytes, ng);
+    const int n = (kLdsPerBlock - gram_mean_bufs(ng) * gram_mean_stage_words(ng) * 4) / gram_piece_bytes(elem_bytes, ng);
     return n < 64 ? n : 64;
 }
 template <typename T>
@@ -242,13 +247,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     constexpr int kElem16 = 16 / sizeof(T);                 // elements per 16-byte piece
     constexpr size_t kStageElems = size_t(256) * M / sizeof(T);   // elements of each row per stage
     constexpr int kInner = sizeof(T) == 4 ? 4 : 1;          // MFMAs per 16-byte register
-    static_assert(2 * kStageWords * 4 >= NT * kGramTile * 8, "stage buffers are reused for the final combine");
+    constexpr int kBufs = kMean ? gram_mean_bufs(NG) : 2;   // stage buffers in LDS
 
     // kMean: the first kQuads threads each own four consecutive columns of a stage (16-byte stores;
     // 8-byte ones by twice the threads measured 2 % slower), and a ring of finished pieces of the
     // mean (one piece = the stage's kStageElems binary32 results) waits in LDS for the next write
     // window: whatever a workgroup's share of the LDS (two workgroups per compute unit) leaves
-    // after the stage buffers.
+    // after the stage buffer.
     constexpr int kQuads = int(kStageElems) / 4;
     static_assert(kQuads <= kBlock, "at most one quad of a stage per thread");
     constexpr int kPieceBytes = int(kStageElems) * 4;
@@ -256,7 +261,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
     static_assert(!kMean || (kHoldStages >= 8 && kStageWords == gram_mean_stage_words(NG) && kPieceBytes == gram_piece_bytes(sizeof(T), NG)),
                   "ring geometry");
     constexpr int kHoldWords = kHoldStages * kPieceBytes / 4;
-    __shared__ __attribute__((aligned(16))) uint32_t stage[2 * kStageWords + kHoldWords];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kBufs * kStageWords + kHoldWords];
+    static_assert((kBufs * kStageWords + kHoldWords) * 4 >= NT * kGramTile * 8, "the LDS is reused for the final combine");
     __shared__ const void *row_table[kGramRows];
     __shared__ int gate_flag[2];
 
@@ -289,7 +295,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
             pred_off[tid] = (r >= 0 && r < kRows ? r : kRows) * kRowWords;
         }
         for (int w = tid; w < kRowWords; w += kBlock)
-            stage[kRows * kRowWords + w] = stage[kStageWords + kRows * kRowWords + w] = 0u;
+            stage[kRows * kRowWords + w] = stage[(kBufs - 1) * kStageWords + kRows * kRowWords + w] = 0u;
     }
     __syncthreads();
 
@@ -479,7 +485,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
                 if (idx + e < P) mean_out[idx + e] = o[e];
     };
     // Pieces of the mean wait in the LDS ring (each thread reads back only what it wrote itself).
-    f32x4_t *const hold = reinterpret_cast<f32x4_t *>(stage + 2 * kStageWords);
+    f32x4_t *const hold = reinterpret_cast<f32x4_t *>(stage + kBufs * kStageWords);
     auto hold_put = [&](int slot, const f32x4_t &o) {
         if (tid < kQuads) hold[slot * kQuads + tid] = o;
     };
@@ -542,9 +548,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2))) voi
                     since_flush = 0;
                     flush();
                 }
-                lstore(buf ^ 1);           // the other buffer was last read before the previous barrier
-                __syncthreads();
-                buf ^= 1;
+                if (kBufs == 2) {
+                    lstore(buf ^ 1);       // the other buffer was last read before the previous barrier
+                    __syncthreads();
+                    buf ^= 1;
+                } else {                   // one buffer: everyone must be done reading it first
+                    __syncthreads();
+                    lstore(0);
+                    __syncthreads();
+                }
                 if (kWrite) {
                     const bool open = gate_flag[parity] != 0;
                     parity ^= 1;
