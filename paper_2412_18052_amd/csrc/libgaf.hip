@@ -326,8 +326,8 @@ gaf_status step_lookahead_impl(gaf_ctx *ctx, float *accum, int32_t *count, const
 template <typename T>
 constexpr int fused_min_count(int groups)
 {
-    constexpr int bf16_min[5] = {2, 2, 2, 4, 6};
-    constexpr int f32_min[5] = {1, 2, 5, 4, 5};
+    constexpr int bf16_min[5] = {2, 2, 2, 4, 4};
+    constexpr int f32_min[5] = {1, 2, 4, 4, 4};
     return sizeof(T) == 2 ? bf16_min[groups] : f32_min[groups];
 }
 // The same for a batch of N gradients. A guess carried over from the previous call is used on
