@@ -253,8 +253,14 @@ struct SmallGramArgs {
     size_t chunk_stride;      // non-zero: sampling launch, see gram_small_range
 };
 
-__host__ __device__ constexpr int small_gram_unroll(int n) { return n <= 4 ? 4 : 2; }   // 16-byte units per thread per tile
-__host__ __device__ constexpr size_t small_gram_tile(int n) { return size_t(kBlock) * small_gram_unroll(n) * 4; }
+// Units of four elements per thread per tile: four, except for five and more binary32 rows, where the loaded
+// values alone would take 128 registers (bfloat16 rows are held packed, two registers per unit; with four units
+// in flight 8 x 1e9 bf16 runs 6 % faster than with two: 2.70 -> 2.53 ms).
+__host__ __device__ constexpr int small_gram_unroll(int n, int elem_bytes) { return n <= 4 || elem_bytes == 2 ? 4 : 2; }
+__host__ __device__ constexpr size_t small_gram_tile(int n, int elem_bytes)
+{
+    return size_t(kBlock) * small_gram_unroll(n, elem_bytes) * 4;
+}
 
 // Inner products of all pairs of N rows over the element range [lo, hi), for the
 // tiles first, first + stride, ... of that range; the workgroup's sums end up in
@@ -276,8 +282,8 @@ __device__ __forceinline__ void gram_small_range(const void *const (&rows)[kSmal
                                                  size_t chunk_stride = 0, int carry_n = 0, int min_count = 0)
 {
     constexpr int NP = N * (N + 1) / 2;
-    constexpr int U = small_gram_unroll(N);
-    constexpr size_t tile = small_gram_tile(N);
+    constexpr int U = small_gram_unroll(N, sizeof(T));
+    constexpr size_t tile = small_gram_tile(N, sizeof(T));
     constexpr size_t kTilesPerChunk = kSampleChunk / tile;
     static_assert(kSampleChunk % tile == 0, "a sample run is a whole number of tiles");
     static_assert(kHalves == 1 || kHalves == 2, "one or two virtual workgroups per workgroup");

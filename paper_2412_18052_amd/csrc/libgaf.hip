@@ -776,7 +776,7 @@ gaf_status bucketed_seg_impl(gaf_ctx *ctx, const void *const *grads, int N, floa
     g.partials = ctx->gram_ws;
     // workgroups per bucket: one per tile of the Gram kernel, capped so that all buckets together
     // stay within the partial-sum table
-    const size_t tile = small_gram_tile(N);
+    const size_t tile = small_gram_tile(N, sizeof(T));
     const int cap = kSegMaxBlocks / B < 256 ? kSegMaxBlocks / B : 256;
     int total = 0;
     for (int b = 0; b < B; ++b) {
